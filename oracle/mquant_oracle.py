@@ -1,0 +1,302 @@
+"""CPU oracle for the MQuant W4A8 linear hot path -- TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, obviously-correct implementation of what the hot path computes,
+written from the MQuant paper (arXiv 2502.00425).  Index work, masks and the
+attention check are numpy; the per-element arithmetic (Hadamard butterflies,
+quantizer, int4 unpack, integer GEMM, dequant) is the C file next to this one,
+loaded with ctypes.  Nothing here imports, links or shares code with the HIP
+library, and the product path never imports this module.
+
+Notation follows the paper: a mixed sequence E of length L (here T rows) with
+visual segment(s); s_v / s_t are the static per-tensor scales of visual / text
+tokens; E^u is the AIFS order (all visual tokens, then all text tokens); M^u is
+the unified causal mask.  0-based half-open spans are used in the API; the one
+function that restates Eq. (6) keeps the paper's 1-based m, n.
+
+Pins (tests/test_oracle_*.py) fix every function to something other than
+itself: H H^T = B I, closed forms, brute force, hand-computed fixtures under
+tests/golden/, the attention-invariance claim of Sec. 3.1.  The paper prints no
+numeric worked example, so there is no paper-printed value to reproduce.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import Iterable, Sequence, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+def _lib() -> ctypes.CDLL:
+    global _LIB
+    if _LIB is None:
+        path = _build.build()
+        lib = ctypes.CDLL(path)
+        i64, i32, f32 = ctypes.c_int64, ctypes.c_int32, ctypes.c_float
+        p = ctypes.c_void_p
+        lib.orc_num_threads.restype = ctypes.c_int
+        lib.orc_fwht_block_f32.argtypes = [p, i32]
+        lib.orc_hadamard_rows_f32.argtypes = [p, i64, i64, i32]
+        lib.orc_msq_quantize.argtypes = [p, i64, i64, i64, f32, f32, p]
+        lib.orc_absmax_f32.argtypes = [p, i64]
+        lib.orc_absmax_f32.restype = f32
+        lib.orc_unpack_w4.argtypes = [p, i64, i64, p]
+        lib.orc_gemm_i8_i4_i32.argtypes = [p, p, i64, i64, i64, p]
+        lib.orc_dequant_f32.argtypes = [p, i64, i64, i64, f32, f32, p, p]
+        _LIB = lib
+    return _LIB
+
+
+def num_threads() -> int:
+    """Host threads the row-parallel loops of the C part use."""
+    return int(_lib().orc_num_threads())
+
+
+def _ptr(a: np.ndarray) -> ctypes.c_void_p:
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _c(a: np.ndarray, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+# --------------------------------------------------------------------------
+# AIFS: token reorder, unified causal mask (Sec. 3.1, Eq. (5), Eq. (6);
+# index form in the appendix on rotary position embedding)
+# --------------------------------------------------------------------------
+
+def aifs_build_perm(T: int, vis_spans: Iterable[Tuple[int, int]]):
+    """Stable partition of row indices: visual rows first, then text rows.
+
+    ``vis_spans`` are 0-based (start, length) pairs.  Returns (perm, inv_perm,
+    V): row i of E^u is row perm[i] of E, V is the number of visual rows.  With
+    one span [m, n] this is the index vector (m..n, 1..m-1, n+1..L) the paper
+    prints; with several spans each modality keeps its original order, which is
+    the natural extension of E^u to "text-image-text-image-..." sequences.
+    """
+    is_vis = np.zeros(T, dtype=bool)
+    for start, length in vis_spans:
+        if length < 0 or start < 0 or start + length > T:
+            raise ValueError("span outside [0, T)")
+        if is_vis[start:start + length].any():
+            raise ValueError("overlapping visual spans")
+        is_vis[start:start + length] = True
+    vis = [i for i in range(T) if is_vis[i]]
+    txt = [i for i in range(T) if not is_vis[i]]
+    perm = np.array(vis + txt, dtype=np.int32).reshape(T)
+    inv = np.empty(T, dtype=np.int32)
+    for new, old in enumerate(perm):
+        inv[old] = new
+    return perm, inv, len(vis)
+
+
+def aifs_permute_rows(x: np.ndarray, perm: np.ndarray) -> np.ndarray:
+    """E^u: row i of the result is row perm[i] of x (a pure copy)."""
+    return np.ascontiguousarray(x[np.asarray(perm, dtype=np.int64)])
+
+
+def causal_mask(T: int) -> np.ndarray:
+    """Eq. (5) as a boolean matrix: entry (i, j) is True (value 0, attend)
+    iff j <= i, False (value -inf) otherwise."""
+    i = np.arange(T).reshape(T, 1)
+    j = np.arange(T).reshape(1, T)
+    return j <= i
+
+
+def aifs_remap_mask(mask: np.ndarray, perm: np.ndarray) -> np.ndarray:
+    """M^u[i, j] = M[perm[i], perm[j]]: token i of E^u may attend token j of
+    E^u exactly when the same two tokens could attend in the original order."""
+    p = np.asarray(perm, dtype=np.int64)
+    return np.ascontiguousarray(mask[p][:, p])
+
+
+def unified_mask_eq6(L: int, m: int, n: int) -> np.ndarray:
+    """Eq. (6) for one visual segment, in the paper's 1-based m..n notation.
+
+    The printed conditions use (n - m) as the number of visual tokens; the
+    segment e^v_m..e^v_n holds n - m + 1 of them, so V = n - m + 1 is used
+    where the paper writes (n - m).  The second bound, n, then equals
+    V + (m - 1): the end of the moved-forward text e^t_1..e^t_{m-1}.
+    Returns a boolean [L, L] matrix (True = 0 = attend) indexed 0-based.
+    """
+    V = n - m + 1
+    out = np.zeros((L, L), dtype=bool)
+    for i in range(1, L + 1):
+        for j in range(1, L + 1):
+            if i <= V:
+                ok = (j <= i) or (V < j <= n)
+            elif i <= n:
+                ok = V < j <= i
+            else:
+                ok = j <= i
+            out[i - 1, j - 1] = ok
+    return out
+
+
+def causal_attention_f64(Q, K, Vv, mask) -> np.ndarray:
+    """Single-head softmax(Q K^T / sqrt(D) + M) V in fp64 with a boolean mask
+    (Eq. (5)); used only to check the attention-invariance claim of AIFS."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    Vv = np.asarray(Vv, dtype=np.float64)
+    D = Q.shape[1]
+    s = Q @ K.T / math.sqrt(D)
+    s = np.where(mask, s, -np.inf)
+    s = s - s.max(axis=1, keepdims=True)
+    e = np.exp(s)
+    a = e / e.sum(axis=1, keepdims=True)
+    return a @ Vv
+
+
+# --------------------------------------------------------------------------
+# Online Hadamard rotation (Sec. 3.2; appendix on the Walsh-Hadamard matrix)
+# --------------------------------------------------------------------------
+
+def hadamard_matrix(B: int) -> np.ndarray:
+    """The +-1 Walsh-Hadamard matrix by the Kronecker recursion
+    H_{2^n} = H_2 (x) H_{2^{n-1}} without the 1/sqrt(2) factors (int64)."""
+    if B < 1 or (B & (B - 1)) != 0:
+        raise ValueError("B must be a power of two")
+    H2 = np.array([[1, 1], [1, -1]], dtype=np.int64)
+    H = np.array([[1]], dtype=np.int64)
+    while H.shape[0] < B:
+        H = np.kron(H2, H)
+    return H
+
+
+def fwht_block_f32(v: np.ndarray) -> np.ndarray:
+    """v * H_B for one block, fp32 butterflies in stage order h = 1, 2, ..."""
+    out = _c(v, np.float32).copy()
+    _lib().orc_fwht_block_f32(_ptr(out), out.shape[0])
+    return out
+
+
+def hadamard_rotate(x: np.ndarray, B: int) -> np.ndarray:
+    """Unnormalised block-diagonal rotation u = x (I (x) H_B) of a [T, K]
+    matrix.  fp16 input is widened to fp32 exactly; the result is fp32.  The
+    orthonormal transform of the paper is u / sqrt(B); that factor is folded
+    into the quantizer's multiplier."""
+    x = np.asarray(x)
+    T, K = x.shape
+    if K % B != 0:
+        raise ValueError("B must divide K")
+    u = np.array(x, dtype=np.float32, order="C", copy=True)
+    _lib().orc_hadamard_rows_f32(_ptr(u), T, K, B)
+    return u
+
+
+# --------------------------------------------------------------------------
+# Quantizer (Eq. (2)) with modality-specific static scales (Eq. (3))
+# --------------------------------------------------------------------------
+
+def quant_multiplier(s: float, B: int) -> np.float32:
+    """c = fp32(1 / (s sqrt(B))), evaluated in double and rounded once."""
+    return np.float32(1.0 / (float(np.float32(s)) * math.sqrt(float(B))))
+
+
+def msq_quantize(u: np.ndarray, V: int, s_vis: float, s_txt: float, B: int) -> np.ndarray:
+    """int8 codes clamp(round_half_even(u / (sqrt(B) s_i)), -128, 127) with
+    s_i = s_v for rows below V (visual) and s_t for the rest (text)."""
+    u = _c(u, np.float32)
+    T, K = u.shape
+    xq = np.empty((T, K), dtype=np.int8)
+    _lib().orc_msq_quantize(_ptr(u), T, K, V,
+                            quant_multiplier(s_vis, B), quant_multiplier(s_txt, B), _ptr(xq))
+    return xq
+
+
+def rotated_absmax(x_calib: np.ndarray, B: int) -> np.float32:
+    """max |u| over the unnormalised rotation of calibration rows."""
+    u = hadamard_rotate(x_calib, B)
+    return np.float32(_lib().orc_absmax_f32(_ptr(u), u.size))
+
+
+def static_scale_from_absmax(absmax_u: float, B: int) -> np.float32:
+    """s = max|x_rot| / (2^{b-1} - 1) with b = 8 (Eq. (2)); x_rot = u/sqrt(B)."""
+    return np.float32(float(np.float32(absmax_u)) / math.sqrt(float(B)) / 127.0)
+
+
+def calibrate_static_scale(x_calib: np.ndarray, B: int) -> np.float32:
+    """Static per-tensor scale of one modality from its calibration rows."""
+    return static_scale_from_absmax(rotated_absmax(x_calib, B), B)
+
+
+# --------------------------------------------------------------------------
+# W4A8 integer GEMM and dequantisation
+# --------------------------------------------------------------------------
+
+def unpack_w4(packed: np.ndarray) -> np.ndarray:
+    """Canonical [N, K/2] bytes -> int8 [N, K] in [-8, 7] (even k = low nibble,
+    two's complement)."""
+    packed = _c(packed, np.uint8)
+    N, K2 = packed.shape
+    wq = np.empty((N, 2 * K2), dtype=np.int8)
+    _lib().orc_unpack_w4(_ptr(packed), N, 2 * K2, _ptr(wq))
+    return wq
+
+
+def gemm_i8_i4_i32(xq: np.ndarray, wq: np.ndarray) -> np.ndarray:
+    """acc[i, n] = sum_k xq[i, k] wq[n, k], exact int32."""
+    xq = _c(xq, np.int8)
+    wq = _c(wq, np.int8)
+    T, K = xq.shape
+    N, K2 = wq.shape
+    if K != K2:
+        raise ValueError("K mismatch")
+    acc = np.empty((T, N), dtype=np.int32)
+    _lib().orc_gemm_i8_i4_i32(_ptr(xq), _ptr(wq), T, N, K, _ptr(acc))
+    return acc
+
+
+def dequant(acc: np.ndarray, V: int, s_vis: float, s_txt: float, w_scale: np.ndarray):
+    """(fp32 reference, fp16 output): ref = (float(acc) s_i) w_scale[n]."""
+    acc = _c(acc, np.int32)
+    T, N = acc.shape
+    ws = np.asarray(w_scale).astype(np.float32)   # fp16 -> fp32 is exact
+    ws = _c(ws, np.float32)
+    ref = np.empty((T, N), dtype=np.float32)
+    _lib().orc_dequant_f32(_ptr(acc), T, N, V, np.float32(s_vis), np.float32(s_txt),
+                           _ptr(ws), _ptr(ref))
+    return ref, ref.astype(np.float16)
+
+
+def w4a8_linear(x: np.ndarray, vis_spans: Sequence[Tuple[int, int]], w_packed: np.ndarray,
+                w_scale: np.ndarray, s_vis: float, s_txt: float, B: int,
+                rows=None, cols=None) -> dict:
+    """The whole path on one linear, every intermediate kept.
+
+    x is fp16 [T, K] in ORIGINAL token order.  ``rows`` / ``cols`` (index
+    arrays into the AIFS-ordered rows and the output channels) restrict the
+    GEMM and dequant to a sub-matrix so large shapes can be spot-checked; the
+    permutation, rotation and quantization always cover every row.
+    """
+    T, K = x.shape
+    perm, inv, V = aifs_build_perm(T, vis_spans)
+    x_u = aifs_permute_rows(x, perm)
+    u = hadamard_rotate(x_u, B)
+    xq = msq_quantize(u, V, s_vis, s_txt, B)
+    out = {"perm": perm, "inv_perm": inv, "V": V, "x_u": x_u, "xq": xq}
+    xs = xq if rows is None else xq[np.asarray(rows)]
+    wp = w_packed if cols is None else w_packed[np.asarray(cols)]
+    ws = w_scale if cols is None else np.asarray(w_scale)[np.asarray(cols)]
+    acc = gemm_i8_i4_i32(xs, unpack_w4(wp))
+    if rows is None:
+        ref, y = dequant(acc, V, s_vis, s_txt, ws)
+    else:
+        # per-row scale choice must follow the AIFS row index, not the position
+        # inside the sample: dequantise visual and text samples separately.
+        r = np.asarray(rows)
+        ref = np.empty(acc.shape, dtype=np.float32)
+        isv = r < V
+        if isv.any():
+            ref[isv], _ = dequant(acc[isv], int(isv.sum()), s_vis, s_txt, ws)
+        if (~isv).any():
+            ref[~isv], _ = dequant(acc[~isv], 0, s_vis, s_txt, ws)
+        y = ref.astype(np.float16)
+    out.update({"acc": acc, "ref": ref, "y": y})
+    return out
