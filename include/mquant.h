@@ -1,0 +1,221 @@
+/*
+ * mquant.h -- C ABI of the MI355X (gfx950) W4A8 linear layer with
+ * modality-specific static activation scales, the hot path of MQuant
+ * (arXiv 2502.00425).
+ *
+ * The path, in the paper's terms:
+ *   E (mixed visual/text tokens)  --AIFS reorder (Sec. 3.1)-->  E^u
+ *   E^u --online block-Hadamard rotation (Sec. 3.2, appendix on the
+ *         Walsh-Hadamard matrix)--> rotated activations
+ *       --static per-tensor int8 quantization, scale s_v for visual rows and
+ *         s_t for text rows (Eq. (2), Eq. (3))--> int8 codes
+ *       --int4-weight x int8-activation GEMM, int32 accumulation (Sec. 4,
+ *         "W4A8 GEMM" / "W4A8 GEMV")--> accumulators
+ *       --dequantisation by s_row * s_w[n] (per-channel weight scale of
+ *         Algorithm 1)--> fp16 output, rows in AIFS order.
+ *
+ * Conventions shared by every entry point
+ *   - Plain C types only.  "dev" pointers are device (HBM) addresses valid on
+ *     the current HIP device, "host" pointers are ordinary host memory.
+ *   - The caller owns every buffer, including workspaces; no entry point
+ *     allocates or frees device memory.
+ *   - Device entry points are asynchronous on `stream` (a hipStream_t passed
+ *     as void*; NULL = the default stream) and never synchronise.
+ *   - Arguments are validated on the host before anything is launched; a
+ *     failed validation launches nothing and returns a negative status.
+ *   - Return value: MQUANT_OK (0) or a negative mquant_status_t.  Nothing
+ *     throws or aborts across this boundary.
+ *   - Zero-sized problems (T == 0, N == 0) are valid no-ops.
+ *   - Matrices are row-major.  fp16 means IEEE binary16.  Leading dimensions
+ *     are in elements.
+ *   - Inputs must be finite; NaN/Inf behaviour is undefined.
+ */
+#ifndef MQUANT_H
+#define MQUANT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MQUANT_OK = 0,
+    MQUANT_ERR_NULL = -1,        /* a required pointer is NULL */
+    MQUANT_ERR_BAD_SHAPE = -2,   /* negative size, leading dimension too small, span outside [0,T), n_vis > T ... */
+    MQUANT_ERR_UNSUPPORTED = -3, /* legal in the paper's terms but outside what these kernels handle */
+    MQUANT_ERR_WORKSPACE = -4,   /* workspace missing or too small */
+    MQUANT_ERR_HIP = -5,         /* a HIP runtime call failed (launch error) */
+    MQUANT_ERR_ALIGNMENT = -6    /* a pointer or leading dimension is not 16-byte aligned */
+} mquant_status_t;
+
+/* One visual segment of the mixed sequence (Sec. 3.1: tokens e^v_m..e^v_n),
+ * 0-based, half-open: rows [start, start+len). */
+typedef struct {
+    int32_t start;
+    int32_t len;
+} mquant_span_t;
+
+typedef void *mquant_stream_t; /* hipStream_t */
+
+/* Library version (major*10000 + minor*100 + patch). */
+int mquant_version(void);
+
+/* Static, NUL-terminated description of a status code. */
+const char *mquant_status_string(int status);
+
+/* -------------------------------------------------------------------------
+ * AIFS (Attention-Invariant Flexible Switching), Sec. 3.1 and the appendix
+ * on rotary position embedding: E^u = (all visual tokens, then all text
+ * tokens), each modality in its original order.
+ * ---------------------------------------------------------------------- */
+
+/*
+ * HOST, synchronous, O(T).  Builds the AIFS index vector.
+ *   vis_host[n_spans] : visual segments, sorted by start, disjoint, inside [0,T)
+ *   perm_host[T]      : out (may be NULL). Row i of E^u is row perm[i] of E;
+ *                       also the position id of row i (the appendix's
+ *                       (m..n, 1..m-1, n+1..L)).
+ *   inv_perm_host[T]  : out (may be NULL). inv_perm[perm[i]] = i.
+ *   n_vis_host        : out (required). Number of visual rows V.
+ * Errors: NULL n_vis_host or (n_spans > 0 and NULL vis_host) -> ERR_NULL;
+ *         T < 0, n_spans < 0, len < 0, unsorted/overlapping/out-of-range
+ *         spans -> ERR_BAD_SHAPE.
+ */
+int mquant_aifs_build_perm(int32_t T, const mquant_span_t *vis_host, int32_t n_spans,
+                           int32_t *perm_host, int32_t *inv_perm_host, int32_t *n_vis_host);
+
+/*
+ * DEVICE.  Row gather x_u[i, :] = x[perm[i], :] for fp16 matrices (Sec. 3.1,
+ * the reorder that replaces slice/concat of interleaved tokens).
+ *   x_dev   : fp16 [T, K], leading dimension ldx  (read)
+ *   x_u_dev : fp16 [T, K], leading dimension ldxu (written); must not alias x
+ *   perm_dev: int32 [T], every entry in [0, T) (not checked on the device
+ *             beyond a clamp: an out-of-range entry reads row 0)
+ * Requirements: K % 8 == 0, ldx % 8 == 0, ldxu % 8 == 0, 16-byte aligned
+ * base pointers (ERR_ALIGNMENT / ERR_UNSUPPORTED otherwise).
+ */
+int mquant_aifs_permute(const void *x_dev, int64_t ldx, void *x_u_dev, int64_t ldxu,
+                        const int32_t *perm_dev, int32_t T, int32_t K, mquant_stream_t stream);
+
+/*
+ * DEVICE.  Unified causal mask M^u[i, j] = M[perm[i], perm[j]] (Eq. (5) ->
+ * Eq. (6)); masks are uint8 [T, T], contiguous, non-zero = may attend.
+ * mask_u must not alias mask.
+ */
+int mquant_aifs_remap_mask(const uint8_t *mask_dev, uint8_t *mask_u_dev, const int32_t *perm_dev,
+                           int32_t T, mquant_stream_t stream);
+
+/* -------------------------------------------------------------------------
+ * Online rotation + modality-specific static quantization (Sec. 3.2; Eq. (2)
+ * with z = 0; Eq. (3)).
+ * ---------------------------------------------------------------------- */
+
+/*
+ * DEVICE.  For every row i of the AIFS-ordered activations and every
+ * contiguous block of had_block channels:
+ *     u   = x_blk * H_B            (H_B the +-1 Walsh-Hadamard matrix of the
+ *                                   Kronecker recursion; fp32 butterflies in
+ *                                   stage order h = 1, 2, 4, ..., B/2)
+ *     xq  = clamp(round_half_even(u * c_i), -128, 127),
+ *     c_i = fp32(1 / (s_i * sqrt(B))),  s_i = s_vis if i < n_vis else s_txt.
+ * The orthonormal 1/sqrt(B) of the rotation is folded into c_i.
+ *   x_dev    : fp16 [*, K], leading dimension ldx.
+ *   perm_dev : NULL -> row i of the output comes from row i of x (x already in
+ *              AIFS order); non-NULL int32 [T] -> from row perm[i] (the gather
+ *              of mquant_aifs_permute fused in).
+ *   xq_dev   : int8 [T, K], contiguous (written).
+ *   had_block: power of two in [1, 1024] dividing K; 1 = no rotation.
+ *   s_vis, s_txt : finite, > 0.
+ * Requirements: K % 8 == 0, ldx % 8 == 0, 16-byte aligned x, 8-byte aligned xq.
+ * Errors: ERR_NULL, ERR_BAD_SHAPE (n_vis outside [0,T], ldx < K, scale <= 0),
+ *         ERR_UNSUPPORTED (had_block not a supported power of two or not
+ *         dividing K, K % 8 != 0), ERR_ALIGNMENT.
+ */
+int mquant_hadamard_quant_act(const void *x_dev, int64_t ldx, const int32_t *perm_dev,
+                              int8_t *xq_dev, int32_t T, int32_t K, int32_t n_vis,
+                              float s_vis, float s_txt, int32_t had_block,
+                              mquant_stream_t stream);
+
+/*
+ * DEVICE.  Calibration statistic of Algorithm 1 (activation scale from
+ * calibration samples; Eq. (2): s = max|x| / 127): the maximum |u| over the
+ * unnormalised rotation of all T rows, combined into *absmax_dev with max().
+ * The caller zeroes *absmax_dev (a float in device memory) beforehand and
+ * derives s = absmax / sqrt(B) / 127.  Same requirements as
+ * mquant_hadamard_quant_act.
+ */
+int mquant_hadamard_absmax(const void *x_dev, int64_t ldx, int32_t T, int32_t K,
+                           int32_t had_block, float *absmax_dev, mquant_stream_t stream);
+
+/* -------------------------------------------------------------------------
+ * W4A8 GEMM / GEMV (Sec. 4: "W4A8 GEMM", "custom W4A8 GEMV kernel") with the
+ * fused dequantisation y = acc * s_row * s_w[n].
+ * ---------------------------------------------------------------------- */
+
+/*
+ * Size in bytes of the kernel-private weight layout for an [N, K] int4
+ * matrix (N padded to a multiple of 32).  Negative status on bad shape.
+ */
+int64_t mquant_w4_prepacked_bytes(int32_t N, int32_t K);
+
+/*
+ * DEVICE, one-off (weights are static).  Reorders the canonical int4 storage
+ *   w_canonical_dev : uint8 [N, K/2]; byte n*K/2 + k/2 holds channel k of
+ *                     output row n, even k in the low nibble, odd k in the
+ *                     high nibble, 4-bit two's complement in [-8, 7]
+ * into the tile order the GEMM/GEMV kernels stream
+ * (mquant_w4_prepacked_bytes(N, K) bytes, 16-byte aligned).
+ * Requirements: K % 64 == 0 (ERR_UNSUPPORTED otherwise), K <= 65536.
+ */
+int mquant_w4_prepack(const uint8_t *w_canonical_dev, uint8_t *w_prepacked_dev,
+                      int32_t N, int32_t K, mquant_stream_t stream);
+
+/* Workspace mquant_w4a8_gemm needs for this shape (may be 0). */
+int64_t mquant_w4a8_workspace_bytes(int32_t T, int32_t N, int32_t K);
+
+/*
+ * DEVICE.  acc[i, n] = sum_k xq[i, k] * wq[n, k] in int32 (exact), then
+ * y[i, n] = fp16( (float(acc) * s_i) * float(w_scale[n]) ), s_i = s_vis for
+ * rows i < n_vis and s_txt otherwise.  Small T (decode) is routed to a
+ * weight-streaming GEMV kernel, large T (prefill) to the MFMA GEMM.
+ *   xq_dev         : int8 [T, K] contiguous, 16-byte aligned
+ *   w_prepacked_dev: output of mquant_w4_prepack for the same (N, K)
+ *   w_scale_dev    : fp16 [N]
+ *   y_dev          : fp16 [T, N], leading dimension ldy >= N (written)
+ *   acc_out_dev    : NULL, or int32 [T, N] contiguous that receives the raw
+ *                    accumulators (for verification; costs extra traffic)
+ *   workspace_dev  : at least mquant_w4a8_workspace_bytes(T, N, K) bytes,
+ *                    256-byte aligned; may be NULL when that size is 0.
+ *                    Contents are scratch; concurrent calls must not share it.
+ * Errors: ERR_NULL, ERR_BAD_SHAPE, ERR_UNSUPPORTED (K % 64 != 0,
+ *         K > 65536), ERR_WORKSPACE, ERR_ALIGNMENT.
+ */
+int mquant_w4a8_gemm(const int8_t *xq_dev, const uint8_t *w_prepacked_dev,
+                     const void *w_scale_dev, void *y_dev, int64_t ldy, int32_t *acc_out_dev,
+                     int32_t T, int32_t N, int32_t K, int32_t n_vis, float s_vis, float s_txt,
+                     void *workspace_dev, int64_t workspace_bytes, mquant_stream_t stream);
+
+/* Workspace of the fused prefill entry: the int8 activations plus whatever
+ * mquant_w4a8_gemm needs. */
+int64_t mquant_w4a8_linear_prefill_workspace_bytes(int32_t T, int32_t N, int32_t K);
+
+/*
+ * DEVICE.  The whole path for one linear layer at prefill: x in ORIGINAL
+ * token order plus the AIFS index vector -> y in AIFS order.  Equivalent to
+ * mquant_hadamard_quant_act(x, perm) into the workspace followed by
+ * mquant_w4a8_gemm; the standalone row permute never touches memory.
+ * perm_dev may be NULL when x is already in AIFS order.
+ */
+int mquant_w4a8_linear_prefill(const void *x_dev, int64_t ldx, const int32_t *perm_dev,
+                               const uint8_t *w_prepacked_dev, const void *w_scale_dev,
+                               void *y_dev, int64_t ldy,
+                               int32_t T, int32_t N, int32_t K, int32_t n_vis,
+                               float s_vis, float s_txt, int32_t had_block,
+                               void *workspace_dev, int64_t workspace_bytes,
+                               mquant_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MQUANT_H */

@@ -1,0 +1,214 @@
+"""Thin ctypes binding of libmquant.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (without the
+``mquant_`` prefix) and does no arithmetic of the method: tensors are handed
+over as device pointers, the stream is torch's current HIP stream.  PyTorch is
+used for device memory and streams only.  There is no CPU fallback: if the HIP
+library is missing or cannot be loaded the import of this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libmquant.so")
+
+EXPORTS = (
+    "mquant_version", "mquant_status_string", "mquant_aifs_build_perm", "mquant_aifs_permute",
+    "mquant_aifs_remap_mask", "mquant_hadamard_quant_act", "mquant_hadamard_absmax",
+    "mquant_w4_prepacked_bytes", "mquant_w4_prepack", "mquant_w4a8_workspace_bytes",
+    "mquant_w4a8_gemm", "mquant_w4a8_linear_prefill_workspace_bytes", "mquant_w4a8_linear_prefill",
+)
+
+OK, ERR_NULL, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGNMENT = 0, -1, -2, -3, -4, -5, -6
+
+
+class MQuantError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class Span(ctypes.Structure):
+    _fields_ = [("start", ctypes.c_int32), ("len", ctypes.c_int32)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2502_00425_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i32, i64, f32, p = ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
+    lib.mquant_version.restype = ctypes.c_int
+    lib.mquant_status_string.restype = ctypes.c_char_p
+    lib.mquant_status_string.argtypes = [ctypes.c_int]
+    lib.mquant_aifs_build_perm.argtypes = [i32, p, i32, p, p, p]
+    lib.mquant_aifs_permute.argtypes = [p, i64, p, i64, p, i32, i32, p]
+    lib.mquant_aifs_remap_mask.argtypes = [p, p, p, i32, p]
+    lib.mquant_hadamard_quant_act.argtypes = [p, i64, p, p, i32, i32, i32, f32, f32, i32, p]
+    lib.mquant_hadamard_absmax.argtypes = [p, i64, i32, i32, i32, p, p]
+    lib.mquant_w4_prepacked_bytes.restype = i64
+    lib.mquant_w4_prepacked_bytes.argtypes = [i32, i32]
+    lib.mquant_w4_prepack.argtypes = [p, p, i32, i32, p]
+    lib.mquant_w4a8_workspace_bytes.restype = i64
+    lib.mquant_w4a8_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.mquant_w4a8_gemm.argtypes = [p, p, p, p, i64, p, i32, i32, i32, i32, f32, f32, p, i64, p]
+    lib.mquant_w4a8_linear_prefill_workspace_bytes.restype = i64
+    lib.mquant_w4a8_linear_prefill_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.mquant_w4a8_linear_prefill.argtypes = [p, i64, p, p, p, p, i64, i32, i32, i32, i32, f32, f32,
+                                               i32, p, i64, p]
+    for name in EXPORTS:
+        if name not in ("mquant_status_string", "mquant_w4_prepacked_bytes",
+                        "mquant_w4a8_workspace_bytes", "mquant_w4a8_linear_prefill_workspace_bytes",
+                        "mquant_version"):
+            getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+lib = _load()
+
+
+def status_string(status: int) -> str:
+    return lib.mquant_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib.mquant_version())
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise MQuantError(int(status), where)
+
+
+def _dp(t) -> Optional[int]:
+    """Device (or host) address of a torch tensor; None stays NULL."""
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> Optional[int]:
+    import torch
+    return torch.cuda.current_stream().cuda_stream or None
+
+
+# ------------------------------------------------------------------- host
+
+def aifs_build_perm(T: int, vis_spans: Sequence[Tuple[int, int]]):
+    """-> (perm int32[T], inv_perm int32[T], n_vis) as numpy arrays (host)."""
+    n = len(vis_spans)
+    arr = (Span * max(n, 1))()
+    for i, (s, l) in enumerate(vis_spans):
+        arr[i].start, arr[i].len = int(s), int(l)
+    perm = np.empty(max(T, 0), dtype=np.int32)
+    inv = np.empty(max(T, 0), dtype=np.int32)
+    n_vis = ctypes.c_int32(0)
+    st = lib.mquant_aifs_build_perm(T, ctypes.cast(arr, ctypes.c_void_p) if n else None, n,
+                                    perm.ctypes.data, inv.ctypes.data,
+                                    ctypes.cast(ctypes.byref(n_vis), ctypes.c_void_p))
+    _check(st, "mquant_aifs_build_perm")
+    return perm, inv, int(n_vis.value)
+
+
+# ----------------------------------------------------------------- device
+
+def aifs_permute(x, perm_dev, out=None):
+    import torch
+    T, K = x.shape
+    if out is None:
+        out = torch.empty((T, K), dtype=x.dtype, device=x.device)
+    _check(lib.mquant_aifs_permute(_dp(x), x.stride(0), _dp(out), out.stride(0), _dp(perm_dev),
+                                   T, K, _stream()), "mquant_aifs_permute")
+    return out
+
+
+def aifs_remap_mask(mask, perm_dev, out=None):
+    import torch
+    T = mask.shape[0]
+    if out is None:
+        out = torch.empty((T, T), dtype=torch.uint8, device=mask.device)
+    _check(lib.mquant_aifs_remap_mask(_dp(mask), _dp(out), _dp(perm_dev), T, _stream()),
+           "mquant_aifs_remap_mask")
+    return out
+
+
+def hadamard_quant_act(x, n_vis: int, s_vis: float, s_txt: float, had_block: int,
+                       perm_dev=None, out=None, T: Optional[int] = None):
+    import torch
+    rows, K = x.shape
+    T = rows if T is None else T
+    if out is None:
+        out = torch.empty((T, K), dtype=torch.int8, device=x.device)
+    _check(lib.mquant_hadamard_quant_act(_dp(x), x.stride(0), _dp(perm_dev), _dp(out), T, K, n_vis,
+                                         s_vis, s_txt, had_block, _stream()),
+           "mquant_hadamard_quant_act")
+    return out
+
+
+def hadamard_absmax(x, had_block: int, absmax_dev):
+    T, K = x.shape
+    _check(lib.mquant_hadamard_absmax(_dp(x), x.stride(0), T, K, had_block, _dp(absmax_dev),
+                                      _stream()), "mquant_hadamard_absmax")
+    return absmax_dev
+
+
+def w4_prepacked_bytes(N: int, K: int) -> int:
+    n = int(lib.mquant_w4_prepacked_bytes(N, K))
+    if n < 0:
+        raise MQuantError(n, "mquant_w4_prepacked_bytes")
+    return n
+
+
+def w4_prepack(w_canonical, out=None):
+    import torch
+    N, K2 = w_canonical.shape
+    K = 2 * K2
+    if out is None:
+        out = torch.empty(w4_prepacked_bytes(N, K), dtype=torch.uint8, device=w_canonical.device)
+    _check(lib.mquant_w4_prepack(_dp(w_canonical), _dp(out), N, K, _stream()), "mquant_w4_prepack")
+    return out
+
+
+def w4a8_workspace_bytes(T: int, N: int, K: int) -> int:
+    n = int(lib.mquant_w4a8_workspace_bytes(T, N, K))
+    if n < 0:
+        raise MQuantError(n, "mquant_w4a8_workspace_bytes")
+    return n
+
+
+def w4a8_gemm(xq, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float, s_txt: float,
+              out=None, acc_out=None, workspace=None):
+    import torch
+    T, K = xq.shape
+    if out is None:
+        out = torch.empty((T, N), dtype=torch.float16, device=xq.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.mquant_w4a8_gemm(_dp(xq), _dp(w_prepacked), _dp(w_scale), _dp(out), out.stride(0),
+                                _dp(acc_out), T, N, K, n_vis, s_vis, s_txt, _dp(workspace),
+                                ws_bytes, _stream()), "mquant_w4a8_gemm")
+    return out
+
+
+def w4a8_linear_prefill_workspace_bytes(T: int, N: int, K: int) -> int:
+    n = int(lib.mquant_w4a8_linear_prefill_workspace_bytes(T, N, K))
+    if n < 0:
+        raise MQuantError(n, "mquant_w4a8_linear_prefill_workspace_bytes")
+    return n
+
+
+def w4a8_linear_prefill(x, perm_dev, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float,
+                        s_txt: float, had_block: int, workspace, out=None):
+    import torch
+    T, K = x.shape
+    if out is None:
+        out = torch.empty((T, N), dtype=torch.float16, device=x.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.mquant_w4a8_linear_prefill(_dp(x), x.stride(0), _dp(perm_dev), _dp(w_prepacked),
+                                          _dp(w_scale), _dp(out), out.stride(0), T, N, K, n_vis,
+                                          s_vis, s_txt, had_block, _dp(workspace), ws_bytes,
+                                          _stream()), "mquant_w4a8_linear_prefill")
+    return out

@@ -1,0 +1,225 @@
+// Online block-Hadamard rotation fused with the modality-specific static int8
+// quantizer (MQuant Sec. 3.2; Eq. (2) with z = 0; Eq. (3)), plus the rotated
+// absmax statistic used to calibrate the static scales (Algorithm 1).
+//
+// One wavefront owns 512 contiguous channels of one row (1024 when the block
+// is 1024): lane l holds channels 8l..8l+7, so index bits 0-2 live in a lane's
+// registers and bits 3-8 across the 64 lanes.  The butterflies run in the fixed
+// stage order h = 1, 2, 4, ..., B/2, one fp32 add or subtract each, which is
+// what makes the int8 codes reproducible bit for bit.  The kernel is bound by
+// HBM traffic: 2 bytes read and 1 byte written per element.
+#include <hip/hip_fp16.h>
+#include <math.h>
+
+#include "mquant_internal.h"
+
+using namespace mquant;
+
+namespace {
+
+template <int B>
+__device__ __forceinline__ void register_stages(float (&v)[8])
+{
+    // h = 1, 2, 4 inside the lane's eight contiguous channels.
+#pragma unroll
+    for (int h = 1; h < 8 && h < B; h <<= 1) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if ((j & h) == 0) {
+                const float a = v[j], b = v[j + h];
+                v[j] = a + b;
+                v[j + h] = a - b;
+            }
+        }
+    }
+}
+
+template <int B>
+__device__ __forceinline__ void lane_stages(float (&v)[8], int lane)
+{
+    // h = 8, 16, ..., min(B, 512)/2: partner lane differs in bit h/8.  The lane
+    // holding the lower index keeps a + b, the other one a - b with a the
+    // lower-index value.
+#pragma unroll
+    for (int m = 1; m < 64 && 8 * m < B; m <<= 1) {
+        const bool upper = (lane & m) != 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float other = __shfl_xor(v[j], m, kWave);
+            v[j] = upper ? (other - v[j]) : (v[j] + other);
+        }
+    }
+}
+
+template <int B, bool ABSMAX>
+__global__ __launch_bounds__(256) void hadamard_quant_kernel(
+    const __half *__restrict__ x, int64_t ldx, const int32_t *__restrict__ perm,
+    int8_t *__restrict__ xq, int32_t T, int32_t K, int32_t n_vis, float c_vis, float c_txt,
+    int32_t segs_per_row, float *__restrict__ absmax)
+{
+    constexpr int C = B > 512 ? B / 512 : 1;      // 512-channel chunks per wave segment
+    constexpr int SEG = 512 * C;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave0 = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int64_t total = static_cast<int64_t>(T) * segs_per_row;
+    float wave_max = 0.0f;
+
+    for (int64_t seg = wave0; seg < total; seg += static_cast<int64_t>(gridDim.x) * 4) {
+        const int32_t i = static_cast<int32_t>(seg / segs_per_row);
+        const int32_t sidx = static_cast<int32_t>(seg - static_cast<int64_t>(i) * segs_per_row);
+        int32_t src = i;
+        if (perm != nullptr) {
+            src = perm[i];
+            src = (src < 0 || src >= T) ? 0 : src;
+        }
+        const __half *row = x + static_cast<int64_t>(src) * ldx;
+
+        float v[C][8];
+        bool valid[C];
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const int32_t k0 = sidx * SEG + c * 512 + lane * 8;
+            valid[c] = k0 < K;
+            if (valid[c]) {
+                const uint4 raw = *reinterpret_cast<const uint4 *>(row + k0);
+                const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float2 f = __half22float2(h2[j]);
+                    v[c][2 * j] = f.x;
+                    v[c][2 * j + 1] = f.y;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[c][j] = 0.0f;
+            }
+        }
+
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            register_stages<B>(v[c]);
+            lane_stages<B>(v[c], lane);
+        }
+        // h = 512, ...: across the wave segment's chunks.
+#pragma unroll
+        for (int hc = 1; hc < C; hc <<= 1) {
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                if ((c & hc) == 0) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float a = v[c][j], b = v[c + hc][j];
+                        v[c][j] = a + b;
+                        v[c + hc][j] = a - b;
+                    }
+                }
+            }
+        }
+
+        if constexpr (ABSMAX) {
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                if (valid[c]) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) wave_max = fmaxf(wave_max, fabsf(v[c][j]));
+                }
+            }
+        } else {
+            const float cmul = (i < n_vis) ? c_vis : c_txt;
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                if (valid[c]) {
+                    uint32_t packed[2] = {0u, 0u};
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        float r = __builtin_rintf(v[c][j] * cmul);      // ties to even
+                        r = fminf(fmaxf(r, -128.0f), 127.0f);
+                        const int32_t q = static_cast<int32_t>(r);
+                        packed[j >> 2] |= (static_cast<uint32_t>(q) & 0xFFu) << (8 * (j & 3));
+                    }
+                    const int64_t k0 = static_cast<int64_t>(sidx) * SEG + c * 512 + lane * 8;
+                    *reinterpret_cast<uint2 *>(xq + static_cast<int64_t>(i) * K + k0) =
+                        make_uint2(packed[0], packed[1]);
+                }
+            }
+        }
+    }
+
+    if constexpr (ABSMAX) {
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) wave_max = fmaxf(wave_max, __shfl_xor(wave_max, m, kWave));
+        // non-negative floats order like their bit patterns
+        if (lane == 0) atomicMax(reinterpret_cast<unsigned int *>(absmax), __float_as_uint(wave_max));
+    }
+}
+
+template <bool ABSMAX>
+int launch(const void *x, int64_t ldx, const int32_t *perm, int8_t *xq, int32_t T, int32_t K,
+           int32_t n_vis, float c_vis, float c_txt, int32_t B, float *absmax, hipStream_t stream)
+{
+    const int32_t seg = B > 512 ? B : 512;
+    const int32_t segs_per_row = static_cast<int32_t>(ceil_div(K, seg));
+    const int64_t total = static_cast<int64_t>(T) * segs_per_row;
+    int64_t blocks = ceil_div(total, 4);
+    if (blocks > (1 << 20)) blocks = 1 << 20;
+    const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+    const __half *xh = static_cast<const __half *>(x);
+#define MQ_CASE(BV)                                                                          \
+    case BV:                                                                                 \
+        hipLaunchKernelGGL((hadamard_quant_kernel<BV, ABSMAX>), grid, block, 0, stream, xh,  \
+                           ldx, perm, xq, T, K, n_vis, c_vis, c_txt, segs_per_row, absmax);  \
+        break;
+    switch (B) {
+        MQ_CASE(1) MQ_CASE(2) MQ_CASE(4) MQ_CASE(8) MQ_CASE(16) MQ_CASE(32) MQ_CASE(64)
+        MQ_CASE(128) MQ_CASE(256) MQ_CASE(512) MQ_CASE(1024)
+    default: return MQUANT_ERR_UNSUPPORTED;
+    }
+#undef MQ_CASE
+    return launch_status();
+}
+
+int check_common(const void *x, int64_t ldx, int32_t T, int32_t K, int32_t B)
+{
+    if (T < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
+    if (B < 1 || B > 1024 || (B & (B - 1)) != 0) return MQUANT_ERR_UNSUPPORTED;
+    if (K % B != 0 || K % 8 != 0) return MQUANT_ERR_UNSUPPORTED;
+    if (T == 0 || K == 0) return MQUANT_OK;
+    if (!x) return MQUANT_ERR_NULL;
+    if (ldx < K) return MQUANT_ERR_BAD_SHAPE;
+    if (ldx % 8 != 0 || !aligned_to(x, 16)) return MQUANT_ERR_ALIGNMENT;
+    return MQUANT_OK;
+}
+
+}  // namespace
+
+extern "C" int mquant_hadamard_quant_act(const void *x, int64_t ldx, const int32_t *perm,
+                                         int8_t *xq, int32_t T, int32_t K, int32_t n_vis,
+                                         float s_vis, float s_txt, int32_t had_block,
+                                         mquant_stream_t stream)
+{
+    const int st = check_common(x, ldx, T, K, had_block);
+    if (st != MQUANT_OK) return st;
+    if (n_vis < 0 || n_vis > T) return MQUANT_ERR_BAD_SHAPE;
+    if (!(s_vis > 0.0f) || !(s_txt > 0.0f) || !isfinite(s_vis) || !isfinite(s_txt))
+        return MQUANT_ERR_BAD_SHAPE;
+    if (T == 0 || K == 0) return MQUANT_OK;
+    if (!xq) return MQUANT_ERR_NULL;
+    if (!aligned_to(xq, 8)) return MQUANT_ERR_ALIGNMENT;
+    // 1 / (s * sqrt(B)) in double, rounded once to fp32.
+    const double rb = sqrt(static_cast<double>(had_block));
+    const float c_vis = static_cast<float>(1.0 / (static_cast<double>(s_vis) * rb));
+    const float c_txt = static_cast<float>(1.0 / (static_cast<double>(s_txt) * rb));
+    return launch<false>(x, ldx, perm, xq, T, K, n_vis, c_vis, c_txt, had_block, nullptr,
+                         static_cast<hipStream_t>(stream));
+}
+
+extern "C" int mquant_hadamard_absmax(const void *x, int64_t ldx, int32_t T, int32_t K,
+                                      int32_t had_block, float *absmax, mquant_stream_t stream)
+{
+    const int st = check_common(x, ldx, T, K, had_block);
+    if (st != MQUANT_OK) return st;
+    if (T == 0 || K == 0) return MQUANT_OK;
+    if (!absmax) return MQUANT_ERR_NULL;
+    return launch<true>(x, ldx, nullptr, nullptr, T, K, 0, 0.0f, 0.0f, had_block, absmax,
+                        static_cast<hipStream_t>(stream));
+}

@@ -1,0 +1,31 @@
+// Internal helpers shared by the HIP translation units of libmquant (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mquant.h"
+
+namespace mquant {
+
+constexpr int kWave = 64;                 // CDNA wavefront width
+
+static inline bool aligned_to(const void *p, uintptr_t a)
+{
+    return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
+}
+
+static inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? MQUANT_OK : MQUANT_ERR_HIP;
+}
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Geometry of the prepacked int4 weight layout (see w4a8_gemm.hip).
+constexpr int kPackN = 32;                // output channels per packed tile (one MFMA N extent)
+constexpr int kPackK = 64;                // input channels per packed tile (two 32x32x32 MFMAs)
+constexpr int kPackTileBytes = kPackN * kPackK / 2;   // 1024: one 16-byte load per lane
+constexpr int kMaxK = 65536;              // 16 * 128 * 8 * K < 2^31 must hold for the x16 unpack
+
+}  // namespace mquant

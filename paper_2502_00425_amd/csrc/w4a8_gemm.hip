@@ -1,0 +1,506 @@
+// W4A8 GEMM / GEMV with fused dequantisation (MQuant Sec. 4: "W4A8 GEMM",
+// "custom W4A8 GEMV kernel"; Eq. (3) for the per-modality activation scale;
+// per-channel weight scale of Algorithm 1).
+//
+//   acc[i, n] = sum_k xq[i, k] * wq[n, k]           (int32, exact)
+//   y[i, n]   = fp16((float(acc) * s_i) * w_scale[n]),  s_i = s_vis (i < n_vis) or s_txt
+//
+// Matrix core: v_mfma_i32_32x32x32_i8.  A = int8 activations (M = tokens),
+// B = weights (N = output channels).  Lane l supplies row/column l % 32 and the
+// 16 consecutive k of k-group l / 32; it receives column l % 32 of the 32x32
+// result, rows (r / 4) * 8 + (l / 32) * 4 + r % 4 for accumulator register r.
+//
+// Prepacked weights.  A tile is 32 output channels x 64 input channels = 1 KiB,
+// stored as [n_tile][k_tile][lane][16 bytes]: lane (n % 32) + 32 * g holds the
+// 32 channels k = 64 * k_tile + 32 * g .. + 31 of output row n, i.e. exactly
+// the B operands of two MFMAs, fetched with one 16-byte load per lane (1 KiB
+// contiguous per wavefront).  Inside each dword of 8 channels the nibbles are
+// interleaved (nibble 2j = channel j, nibble 2j+1 = channel 4+j) so that
+//     lo = (v << 4) & 0xF0F0F0F0   -> bytes 16*w[0..3]
+//     hi =  v       & 0xF0F0F0F0   -> bytes 16*w[4..7]
+// are ready-made int8 operands.  The accumulator therefore holds 16 * acc and
+// is shifted right by 4 (exact) in the epilogue; 16 * 128 * 8 * K < 2^31 for
+// K <= 65536.
+#include <hip/hip_fp16.h>
+#include <math.h>
+
+#include "mquant_internal.h"
+
+using namespace mquant;
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+namespace {
+
+// ------------------------------------------------------------------ prepack
+
+__global__ __launch_bounds__(256) void prepack_kernel(
+    const uint8_t *__restrict__ w, uint32_t *__restrict__ out, int32_t N, int32_t K,
+    int32_t n_tiles, int32_t k_tiles)
+{
+    const int64_t total = static_cast<int64_t>(n_tiles) * k_tiles * 64 * 4;     // dwords
+    for (int64_t o = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; o < total;
+         o += static_cast<int64_t>(gridDim.x) * 256) {
+        const int d = static_cast<int>(o & 3);
+        const int lane = static_cast<int>((o >> 2) & 63);
+        const int64_t tile = o >> 8;
+        const int32_t kt = static_cast<int32_t>(tile % k_tiles);
+        const int32_t nt = static_cast<int32_t>(tile / k_tiles);
+        const int32_t n = nt * kPackN + (lane & 31);
+        const int32_t k0 = kt * kPackK + (lane >> 5) * 32 + d * 8;
+        uint32_t v = 0;
+        if (n < N) {
+            const uint32_t src =
+                *reinterpret_cast<const uint32_t *>(w + static_cast<int64_t>(n) * (K / 2) + k0 / 2);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t lo = (src >> (4 * j)) & 0xFu;          // channel k0 + j
+                const uint32_t hi = (src >> (4 * (4 + j))) & 0xFu;    // channel k0 + 4 + j
+                v |= lo << (8 * j);
+                v |= hi << (8 * j + 4);
+            }
+        }
+        out[o] = v;
+    }
+}
+
+// ------------------------------------------------------------- shared pieces
+
+// 16 bytes of prepacked weights -> B operands of two MFMAs (values x16).
+__device__ __forceinline__ void unpack_w4x16(const uint4 p, v4i &b0, v4i &b1)
+{
+    b0[0] = static_cast<int>((p.x << 4) & 0xF0F0F0F0u);
+    b0[1] = static_cast<int>(p.x & 0xF0F0F0F0u);
+    b0[2] = static_cast<int>((p.y << 4) & 0xF0F0F0F0u);
+    b0[3] = static_cast<int>(p.y & 0xF0F0F0F0u);
+    b1[0] = static_cast<int>((p.z << 4) & 0xF0F0F0F0u);
+    b1[1] = static_cast<int>(p.z & 0xF0F0F0F0u);
+    b1[2] = static_cast<int>((p.w << 4) & 0xF0F0F0F0u);
+    b1[3] = static_cast<int>(p.w & 0xF0F0F0F0u);
+}
+
+__device__ __forceinline__ v4i as_v4i(const uint4 u)
+{
+    v4i r;
+    r[0] = static_cast<int>(u.x);
+    r[1] = static_cast<int>(u.y);
+    r[2] = static_cast<int>(u.z);
+    r[3] = static_cast<int>(u.w);
+    return r;
+}
+
+// Row of the 32x32 MFMA result held in accumulator register r by k-group g.
+__device__ __forceinline__ int acc_row(int r, int g) { return (r >> 2) * 8 + g * 4 + (r & 3); }
+
+__device__ __forceinline__ void store_out(int32_t acc16, int32_t row, int32_t n, float s_row,
+                                          float ws, __half *y, int64_t ldy, int32_t *acc_out,
+                                          int32_t N)
+{
+    const int32_t acc = acc16 >> 4;                       // exact: acc16 = 16 * acc
+    const float v = (static_cast<float>(acc) * s_row) * ws;
+    y[static_cast<int64_t>(row) * ldy + n] = __float2half_rn(v);
+    if (acc_out) acc_out[static_cast<int64_t>(row) * N + n] = acc;
+}
+
+// ------------------------------------------------------------------- GEMM
+
+// LDS image of one A stage: BM rows x 128 bytes, the eight 16-byte chunks of a
+// row XOR-swizzled with (row & 7) so that both the row-wise writes and the
+// column-wise MFMA fragment reads are bank-conflict free.
+__device__ __forceinline__ int lds_a_offset(int row, int chunk)
+{
+    return row * 128 + ((chunk ^ (row & 7)) << 4);
+}
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
+    const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
+    __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
+    int32_t K, int32_t n_vis, float s_vis, float s_txt, int32_t tiles_m, int32_t tiles_n,
+    int32_t n_tiles32)
+{
+    constexpr int THREADS = WM * WN * 64;
+    constexpr int MT = BM / WM / 32;          // 32x32 tiles per wave along M
+    constexpr int NT = BN / WN / 32;          // ... along N
+    constexpr int A_STAGE = BM * 128;         // bytes
+    constexpr int A_CHUNKS = BM * 8 / THREADS;
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "tile shape");
+    static_assert((BM * 8) % THREADS == 0, "A copy shape");
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    // Tile assignment: consecutive work-group ids are dealt round-robin to the
+    // 8 XCDs, so group ids that share (id % 8) run on one XCD and share its L2.
+    // Give each XCD a contiguous run of tiles; inside a run M varies fastest so
+    // the tiles that reuse one weight panel are neighbours.
+    const int32_t total = tiles_m * tiles_n;
+    int32_t tile = blockIdx.x;
+    {
+        const int32_t per = total / 8, rem = total % 8;
+        const int32_t xcd = tile % 8, local = tile / 8;
+        // XCD x owns per + (x < rem) tiles
+        tile = xcd * per + (xcd < rem ? xcd : rem) + local;
+    }
+    const int32_t tm = tile % tiles_m;
+    const int32_t tn = tile / tiles_m;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % WM;
+    const int wn = wave / WM;
+    const int l32 = lane & 31;
+    const int g = lane >> 5;
+
+    const int32_t row0 = tm * BM;
+    const int32_t k_tiles = K / kPackK;
+    const int32_t k_blocks = K / 128;         // K % 128 == 0 is guaranteed by the host
+
+    v16i acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0;
+
+    // ---- A: global -> registers -> LDS
+    uint4 a_stage[A_CHUNKS];
+    auto load_a = [&](int32_t kb) {
+#pragma unroll
+        for (int it = 0; it < A_CHUNKS; ++it) {
+            const int q = it * THREADS + tid;
+            const int r = q >> 3, c = q & 7;
+            const int32_t row = row0 + r;
+            if (row < T) {
+                a_stage[it] = *reinterpret_cast<const uint4 *>(
+                    xq + static_cast<int64_t>(row) * K + static_cast<int64_t>(kb) * 128 + c * 16);
+            } else {
+                a_stage[it] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    auto store_a = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < A_CHUNKS; ++it) {
+            const int q = it * THREADS + tid;
+            const int r = q >> 3, c = q & 7;
+            *reinterpret_cast<uint4 *>(smem + buf * A_STAGE + lds_a_offset(r, c)) = a_stage[it];
+        }
+    };
+
+    // ---- B: global -> registers, one k-block (two k-tiles) ahead
+    const int32_t nt0 = (tn * BN + wn * (BN / WN)) / 32;       // first 32-channel tile of this wave
+    uint4 b_next[2][NT];
+    auto load_b = [&](int32_t kb) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int32_t ntile = nt0 + nt;
+                if (ntile < n_tiles32) {
+                    b_next[ks][nt] =
+                        wp[(static_cast<int64_t>(ntile) * k_tiles + (kb * 2 + ks)) * 64 + lane];
+                } else {
+                    b_next[ks][nt] = make_uint4(0, 0, 0, 0);
+                }
+            }
+    };
+
+    load_a(0);
+    load_b(0);
+    store_a(0);
+    __syncthreads();
+
+    for (int32_t kb = 0; kb < k_blocks; ++kb) {
+        const int buf = kb & 1;
+        uint4 b_cur[2][NT];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) b_cur[ks][nt] = b_next[ks][nt];
+        if (kb + 1 < k_blocks) {
+            load_a(kb + 1);
+            load_b(kb + 1);
+        }
+
+        const uint8_t *abase = smem + buf * A_STAGE;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v4i a0[MT], a1[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int r = wm * (BM / WM) + mt * 32 + l32;
+                const int c = ks * 4 + g * 2;
+                a0[mt] = as_v4i(*reinterpret_cast<const uint4 *>(abase + lds_a_offset(r, c)));
+                a1[mt] = as_v4i(*reinterpret_cast<const uint4 *>(abase + lds_a_offset(r, c + 1)));
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                v4i b0, b1;
+                unpack_w4x16(b_cur[ks][nt], b0, b1);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    acc[mt][nt] =
+                        __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[mt], b0, acc[mt][nt], 0, 0, 0);
+                    acc[mt][nt] =
+                        __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[mt], b1, acc[mt][nt], 0, 0, 0);
+                }
+            }
+        }
+
+        if (kb + 1 < k_blocks) store_a(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: scale select by row span, per-channel scale, fp16 store
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int32_t n = (nt0 + nt) * 32 + l32;
+        if (n >= N) continue;
+        const float ws = __half2float(w_scale[n]);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int32_t row = row0 + wm * (BM / WM) + mt * 32 + acc_row(r, g);
+                if (row < T) {
+                    const float s_row = row < n_vis ? s_vis : s_txt;
+                    store_out(acc[mt][nt][r], row, n, s_row, ws, y, ldy, acc_out, N);
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------- GEMV
+
+// Decode shape (T <= 32): the weights are streamed once from HBM and nothing
+// is reused, so there is no LDS staging.  One work-group owns one 32-channel
+// tile; its waves split K and the partial accumulators meet in LDS.
+template <int NWAVES>
+__global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
+    const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
+    __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
+    int32_t K, int32_t n_vis, float s_vis, float s_txt)
+{
+    constexpr int UNROLL = 4;
+    __shared__ int32_t red[NWAVES][16][64];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    const int g = lane >> 5;
+    const int32_t ntile = blockIdx.x;
+    const int32_t k_tiles = K / kPackK;
+
+    v16i acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0;
+
+    const uint4 *wtile = wp + static_cast<int64_t>(ntile) * k_tiles * 64 + lane;
+    const bool row_ok = l32 < T;
+    const int8_t *xrow = xq + static_cast<int64_t>(row_ok ? l32 : 0) * K + g * 32;
+
+    for (int32_t kt0 = wave * UNROLL; kt0 < k_tiles; kt0 += NWAVES * UNROLL) {
+        uint4 b[UNROLL], a0[UNROLL], a1[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int32_t kt = kt0 + u;
+            if (kt < k_tiles) {
+                b[u] = wtile[static_cast<int64_t>(kt) * 64];
+                if (row_ok) {
+                    a0[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64);
+                    a1[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64 + 16);
+                } else {
+                    a0[u] = make_uint4(0, 0, 0, 0);
+                    a1[u] = make_uint4(0, 0, 0, 0);
+                }
+            } else {
+                b[u] = make_uint4(0, 0, 0, 0);
+                a0[u] = make_uint4(0, 0, 0, 0);
+                a1[u] = make_uint4(0, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            v4i b0, b1;
+            unpack_w4x16(b[u], b0, b1);
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a0[u]), b0, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a1[u]), b1, acc, 0, 0, 0);
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r];
+    __syncthreads();
+
+    // Each wave finishes a quarter of the accumulator registers.
+    const int32_t n = ntile * 32 + l32;
+    const float ws = n < N ? __half2float(w_scale[n]) : 0.0f;
+    for (int r = wave; r < 16; r += NWAVES) {
+        int32_t sum = 0;
+#pragma unroll
+        for (int w = 0; w < NWAVES; ++w) sum += red[w][r][lane];
+        const int32_t row = acc_row(r, g);
+        if (row < T && n < N) {
+            const float s_row = row < n_vis ? s_vis : s_txt;
+            store_out(sum, row, n, s_row, ws, y, ldy, acc_out, N);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ host side
+
+constexpr int kGemvMaxT = 32;
+
+int check_gemm_args(const void *xq, const void *wp, const void *w_scale, const void *y,
+                    int64_t ldy, int32_t T, int32_t N, int32_t K, int32_t n_vis, float s_vis,
+                    float s_txt)
+{
+    if (T < 0 || N < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
+    if (K % kPackK != 0 || K > kMaxK) return MQUANT_ERR_UNSUPPORTED;
+    if (n_vis < 0 || n_vis > T) return MQUANT_ERR_BAD_SHAPE;
+    if (!(s_vis > 0.0f) || !(s_txt > 0.0f) || !isfinite(s_vis) || !isfinite(s_txt))
+        return MQUANT_ERR_BAD_SHAPE;
+    if (T == 0 || N == 0) return MQUANT_OK;
+    if (ldy < N) return MQUANT_ERR_BAD_SHAPE;
+    if (K == 0) return MQUANT_ERR_UNSUPPORTED;
+    if (!xq || !wp || !w_scale || !y) return MQUANT_ERR_NULL;
+    if (!aligned_to(xq, 16) || !aligned_to(wp, 16) || !aligned_to(w_scale, 2) || !aligned_to(y, 2))
+        return MQUANT_ERR_ALIGNMENT;
+    return MQUANT_OK;
+}
+
+template <int BM, int BN, int WM, int WN>
+int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y, int64_t ldy,
+                int32_t *acc_out, int32_t T, int32_t N, int32_t K, int32_t n_vis, float s_vis,
+                float s_txt, hipStream_t stream)
+{
+    const int32_t tiles_m = static_cast<int32_t>(ceil_div(T, BM));
+    const int32_t tiles_n = static_cast<int32_t>(ceil_div(N, BN));
+    const int32_t n_tiles32 = static_cast<int32_t>(ceil_div(N, kPackN));
+    const size_t lds = 2 * BM * 128;
+    auto kern = w4a8_gemm_kernel<BM, BN, WM, WN>;
+    static bool attr_set = false;       // raising the dynamic LDS limit is idempotent
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                static_cast<int>(lds)) != hipSuccess)
+            return MQUANT_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * 64), lds, stream, xq,
+                       reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
+                       static_cast<__half *>(y), ldy, acc_out, T, N, K, n_vis, s_vis, s_txt,
+                       tiles_m, tiles_n, n_tiles32);
+    return launch_status();
+}
+
+}  // namespace
+
+extern "C" int64_t mquant_w4_prepacked_bytes(int32_t N, int32_t K)
+{
+    if (N < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
+    if (K % kPackK != 0 || K > kMaxK) return MQUANT_ERR_UNSUPPORTED;
+    return ceil_div(N, kPackN) * (K / kPackK) * static_cast<int64_t>(kPackTileBytes);
+}
+
+extern "C" int mquant_w4_prepack(const uint8_t *w, uint8_t *out, int32_t N, int32_t K,
+                                 mquant_stream_t stream)
+{
+    if (N < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
+    if (K % kPackK != 0 || K > kMaxK) return MQUANT_ERR_UNSUPPORTED;
+    if (N == 0 || K == 0) return MQUANT_OK;
+    if (!w || !out) return MQUANT_ERR_NULL;
+    if (!aligned_to(w, 4) || !aligned_to(out, 16)) return MQUANT_ERR_ALIGNMENT;
+    const int32_t n_tiles = static_cast<int32_t>(ceil_div(N, kPackN));
+    const int32_t k_tiles = K / kPackK;
+    const int64_t dwords = static_cast<int64_t>(n_tiles) * k_tiles * 256;
+    int64_t blocks = ceil_div(dwords, 256);
+    if (blocks > (1 << 20)) blocks = 1 << 20;
+    hipLaunchKernelGGL(prepack_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), w, reinterpret_cast<uint32_t *>(out), N, K,
+                       n_tiles, k_tiles);
+    return launch_status();
+}
+
+extern "C" int64_t mquant_w4a8_workspace_bytes(int32_t T, int32_t N, int32_t K)
+{
+    if (T < 0 || N < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
+    if (K % kPackK != 0 || K > kMaxK) return MQUANT_ERR_UNSUPPORTED;
+    return 0;
+}
+
+extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y,
+                                int64_t ldy, int32_t *acc_out, int32_t T, int32_t N, int32_t K,
+                                int32_t n_vis, float s_vis, float s_txt, void *workspace,
+                                int64_t workspace_bytes, mquant_stream_t stream_)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    const int st = check_gemm_args(xq, wp, w_scale, y, ldy, T, N, K, n_vis, s_vis, s_txt);
+    if (st != MQUANT_OK) return st;
+    if (T == 0 || N == 0) return MQUANT_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+
+    if (T <= kGemvMaxT || K % 128 != 0) {
+        // GEMV handles 32 rows per pass; walk taller inputs in slabs of 32 rows
+        // (only reached for K % 128 != 0, which the prefill kernel does not take).
+        for (int32_t t0 = 0; t0 < T; t0 += kGemvMaxT) {
+            const int32_t tt = T - t0 < kGemvMaxT ? T - t0 : kGemvMaxT;
+            int32_t nv = n_vis - t0;
+            nv = nv < 0 ? 0 : (nv > tt ? tt : nv);
+            hipLaunchKernelGGL((w4a8_gemv_kernel<4>), dim3(static_cast<unsigned>(ceil_div(N, 32))),
+                               dim3(256), 0, stream, xq + static_cast<int64_t>(t0) * K,
+                               reinterpret_cast<const uint4 *>(wp),
+                               static_cast<const __half *>(w_scale),
+                               static_cast<__half *>(y) + static_cast<int64_t>(t0) * ldy, ldy,
+                               acc_out ? acc_out + static_cast<int64_t>(t0) * N : nullptr, tt, N, K,
+                               nv, s_vis, s_txt);
+            const int ls = launch_status();
+            if (ls != MQUANT_OK) return ls;
+        }
+        return MQUANT_OK;
+    }
+    return launch_gemm<256, 256, 2, 2>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis, s_vis,
+                                       s_txt, stream);
+}
+
+extern "C" int64_t mquant_w4a8_linear_prefill_workspace_bytes(int32_t T, int32_t N, int32_t K)
+{
+    const int64_t g = mquant_w4a8_workspace_bytes(T, N, K);
+    if (g < 0) return g;
+    const int64_t xq_bytes = ceil_div(static_cast<int64_t>(T) * K, 256) * 256;
+    return xq_bytes + g;
+}
+
+extern "C" int mquant_w4a8_linear_prefill(const void *x, int64_t ldx, const int32_t *perm,
+                                          const uint8_t *wp, const void *w_scale, void *y,
+                                          int64_t ldy, int32_t T, int32_t N, int32_t K,
+                                          int32_t n_vis, float s_vis, float s_txt,
+                                          int32_t had_block, void *workspace,
+                                          int64_t workspace_bytes, mquant_stream_t stream)
+{
+    const int64_t need = mquant_w4a8_linear_prefill_workspace_bytes(T, N, K);
+    if (need < 0) return static_cast<int>(need);
+    if (T == 0 || N == 0) {
+        // still validate the front-end arguments
+        return mquant_hadamard_quant_act(x, ldx, perm, nullptr, 0, K, 0, s_vis, s_txt, had_block,
+                                         stream);
+    }
+    if (!workspace) return MQUANT_ERR_WORKSPACE;
+    if (workspace_bytes < need) return MQUANT_ERR_WORKSPACE;
+    if (!aligned_to(workspace, 256)) return MQUANT_ERR_ALIGNMENT;
+    // Validate the GEMM half before launching the front end so that a failure
+    // launches nothing.
+    int8_t *xq = static_cast<int8_t *>(workspace);
+    int st = check_gemm_args(xq, wp, w_scale, y, ldy, T, N, K, n_vis, s_vis, s_txt);
+    if (st != MQUANT_OK) return st;
+    st = mquant_hadamard_quant_act(x, ldx, perm, xq, T, K, n_vis, s_vis, s_txt, had_block, stream);
+    if (st != MQUANT_OK) return st;
+    const int64_t xq_bytes = ceil_div(static_cast<int64_t>(T) * K, 256) * 256;
+    return mquant_w4a8_gemm(xq, wp, w_scale, y, ldy, nullptr, T, N, K, n_vis, s_vis, s_txt,
+                            static_cast<uint8_t *>(workspace) + xq_bytes, need - xq_bytes, stream);
+}

@@ -1,0 +1,370 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Bit-exact on the permutation, the int8 codes and the
+int32 accumulators; |y - ref| <= 1e-3 * max(|ref|, 2^-14) on the fp16 output
+(ref = the oracle's fp32 dequantised value)."""
+import math
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import mquant_oracle as orc                      # noqa: E402
+from paper_2502_00425_amd import workloads as wl             # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def mq():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2502_00425_amd import binding
+    return binding
+
+
+def say(msg):
+    print(f"[parity] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_y(y_gpu, ref, what):
+    y = y_gpu.astype(np.float32)
+    tol = 1e-3 * np.maximum(np.abs(ref), 2.0 ** -14)
+    bad = np.abs(y - ref) > tol
+    assert not bad.any(), f"{what}: {int(bad.sum())} outputs beyond 1e-3 (first {np.argwhere(bad)[:3].tolist()})"
+    assert (y[ref == 0] == 0).all(), f"{what}: zero reference but non-zero output"
+
+
+def scales_from_calib(inp):
+    B = inp["had_block"]
+    s_vis = float(orc.calibrate_static_scale(inp["calib_vis"], B))
+    s_txt = float(orc.calibrate_static_scale(inp["calib_txt"], B))
+    return s_vis, s_txt
+
+
+# ------------------------------------------------------------------ AIFS
+
+@pytest.mark.parametrize("T,K,spans", [
+    (64, 512, [(8, 48)]),
+    (301, 264, [(5, 100), (150, 7), (290, 11)]),
+    (1, 8, []),
+    (1280, 3584, [(16, 1024)]),
+])
+def test_aifs_permute(mq, T, K, spans):
+    say(f"permute T={T} K={K}")
+    rng = np.random.default_rng(T + K)
+    x = rng.standard_normal((T, K)).astype(np.float16)
+    perm, inv, V = mq.aifs_build_perm(T, spans)
+    operm, _, oV = orc.aifs_build_perm(T, spans)
+    assert V == oV and (perm == operm).all()
+    got = mq.aifs_permute(dev(x), dev(perm)).cpu().numpy()
+    want = orc.aifs_permute_rows(x, operm)
+    assert (got.view(np.uint16) == want.view(np.uint16)).all()
+
+
+def test_aifs_permute_strided(mq):
+    say("permute strided")
+    rng = np.random.default_rng(5)
+    T, K = 37, 72
+    big = rng.standard_normal((T, 96)).astype(np.float16)
+    perm, _, _ = orc.aifs_build_perm(T, [(3, 20)])
+    xd = dev(big)[:, :K]
+    out = torch.zeros((T, 80), dtype=torch.float16, device="cuda")
+    mq.aifs_permute(xd, dev(perm), out=out[:, :K])
+    got = out.cpu().numpy()
+    assert (got[:, :K] == big[perm][:, :K]).all()
+    assert (got[:, K:] == 0).all()
+
+
+@pytest.mark.parametrize("T,spans", [(64, [(8, 48)]), (203, [(9, 50), (100, 31)]), (7, [])])
+def test_aifs_remap_mask_small(mq, T, spans):
+    say(f"mask T={T}")
+    rng = np.random.default_rng(T)
+    perm, _, _ = orc.aifs_build_perm(T, spans)
+    for M in (orc.causal_mask(T), rng.integers(0, 2, size=(T, T)).astype(bool)):
+        got = mq.aifs_remap_mask(dev(M.astype(np.uint8)), dev(perm)).cpu().numpy()
+        assert (got == orc.aifs_remap_mask(M, perm).astype(np.uint8)).all()
+
+
+def test_aifs_remap_mask_config2(mq):
+    """4096 x 4096 causal mask of config 2: equal to the oracle's remap (which
+    the CPU tests tie to Eq. (6) and to attention invariance)."""
+    say("mask config2 4096")
+    w = wl.workload(2)
+    T = w.T
+    perm, _, V = orc.aifs_build_perm(T, w.vis_spans)
+    M = orc.causal_mask(T)
+    got = mq.aifs_remap_mask(dev(M.astype(np.uint8)), dev(perm)).cpu().numpy().astype(bool)
+    assert (got == orc.aifs_remap_mask(M, perm)).all()
+    assert (got.sum(axis=1) == perm + 1).all()
+
+
+# --------------------------------------------------- rotation + quantizer
+
+@pytest.mark.parametrize("T,K,B,V,use_perm", [
+    (64, 512, 512, 48, True),
+    (33, 1024, 1024, 10, False),
+    (70, 640, 128, 0, True),
+    (70, 640, 128, 70, False),
+    (19, 1536, 256, 7, True),
+    (5, 64, 16, 2, False),
+    (9, 72, 8, 4, True),
+    (9, 40, 4, 4, False),
+    (9, 40, 2, 4, False),
+    (6, 24, 1, 3, True),
+    (300, 3584, 512, 111, True),
+])
+def test_hadamard_quant_bit_exact(mq, T, K, B, V, use_perm):
+    say(f"hadamard_quant T={T} K={K} B={B} V={V} perm={use_perm}")
+    rng = np.random.default_rng(1000 * B + T)
+    x = rng.standard_normal((T, K)).astype(np.float32)
+    x[: T // 2] *= 20.0
+    x[:, 3 % K] *= 50.0
+    x = x.astype(np.float16)
+    s_vis, s_txt = 0.37 * math.sqrt(1.0), 0.021
+    if use_perm:
+        spans = [(min(T // 3, T - V), V)] if V else []
+        perm, _, V2 = orc.aifs_build_perm(T, spans)
+        assert V2 == V
+        permd = dev(perm)
+        x_u = orc.aifs_permute_rows(x, perm)
+    else:
+        permd = None
+        x_u = x
+    want = orc.msq_quantize(orc.hadamard_rotate(x_u, B), V, s_vis, s_txt, B)
+    got = mq.hadamard_quant_act(dev(x), V, s_vis, s_txt, B, perm_dev=permd).cpu().numpy()
+    assert got.dtype == np.int8
+    assert (got == want).all(), f"{int((got != want).sum())} codes differ"
+    assert np.abs(want.astype(np.int32)).max() > 20          # the case is not degenerate
+
+
+def test_hadamard_quant_strided_input_and_saturation(mq):
+    say("hadamard_quant strided + saturation")
+    rng = np.random.default_rng(77)
+    T, K, B = 21, 512, 512
+    big = (rng.standard_normal((T, 1024)) * 300).astype(np.float16)
+    x = big[:, :K]
+    s = 0.05                                                # far too small: most codes clamp
+    want = orc.msq_quantize(orc.hadamard_rotate(np.ascontiguousarray(x), B), 9, s, s * 3, B)
+    got = mq.hadamard_quant_act(dev(big)[:, :K], 9, s, s * 3, B).cpu().numpy()
+    assert (got == want).all()
+    assert (want == 127).sum() > 100 and (want == -128).sum() > 100
+
+
+@pytest.mark.parametrize("B", [1, 16, 128, 512, 1024])
+def test_hadamard_absmax(mq, B):
+    say(f"absmax B={B}")
+    rng = np.random.default_rng(B)
+    x = (rng.standard_normal((50, 2048)) * 7).astype(np.float16)
+    want = orc.rotated_absmax(x, B)
+    out = torch.zeros(1, dtype=torch.float32, device="cuda")
+    mq.hadamard_absmax(dev(x), B, out)
+    assert np.float32(out.item()) == want
+
+
+# -------------------------------------------------------- prepack + GEMM
+
+def run_linear_gpu(mq, inp, s_vis, s_txt, want_acc=True, fused=False):
+    T, K, N, B = inp["T"], inp["K"], inp["N"], inp["had_block"]
+    perm, inv, V = mq.aifs_build_perm(T, inp["vis_spans"])
+    xd = dev(inp["x"])
+    permd = dev(perm)
+    wp = mq.w4_prepack(dev(inp["w_packed"]))
+    wsd = dev(inp["w_scale"])
+    out = {"perm": perm, "V": V}
+    if fused:
+        ws = torch.empty(mq.w4a8_linear_prefill_workspace_bytes(T, N, K), dtype=torch.uint8, device="cuda")
+        y = mq.w4a8_linear_prefill(xd, permd, wp, wsd, N, V, s_vis, s_txt, B, ws)
+        out["xq"] = ws[: T * K].view(torch.int8).reshape(T, K)
+    else:
+        xq = mq.hadamard_quant_act(xd, V, s_vis, s_txt, B, perm_dev=permd)
+        out["xq"] = xq
+        nws = mq.w4a8_workspace_bytes(T, N, K)
+        ws = torch.empty(max(nws, 1), dtype=torch.uint8, device="cuda") if nws else None
+        acc = torch.empty((T, N), dtype=torch.int32, device="cuda") if want_acc else None
+        y = mq.w4a8_gemm(xq, wp, wsd, N, V, s_vis, s_txt, acc_out=acc, workspace=ws)
+        out["acc"] = acc
+    out["y"] = y
+    torch.cuda.synchronize()
+    return out
+
+
+def test_config0_full(mq):
+    say("config 0 full")
+    w = wl.workload(0)
+    inp = wl.make_linear_inputs(w, "lin")
+    s_vis, s_txt = scales_from_calib(inp)
+    o = orc.w4a8_linear(inp["x"], inp["vis_spans"], inp["w_packed"], inp["w_scale"], s_vis, s_txt, w.had_block)
+    for fused in (False, True):
+        g = run_linear_gpu(mq, inp, s_vis, s_txt, fused=fused)
+        assert (g["perm"] == o["perm"]).all() and g["V"] == o["V"] == 48
+        assert (g["xq"].cpu().numpy() == o["xq"]).all()
+        if not fused:
+            assert (g["acc"].cpu().numpy() == o["acc"]).all()
+        check_y(g["y"].cpu().numpy(), o["ref"], f"config0 fused={fused}")
+
+
+@pytest.mark.parametrize("T,N,K,V", [
+    (300, 544, 384, 120),       # two M tiles, three N tiles, ragged both ways
+    (257, 100, 128, 257),       # N below one tile, T one row past a tile
+    (512, 256, 1024, 0),
+    (40, 72, 256, 13),          # above the GEMV limit, far below one tile
+    (130, 300, 192, 64),        # K % 128 != 0
+])
+def test_gemm_small_shapes_full(mq, T, N, K, V):
+    say(f"gemm T={T} N={N} K={K} V={V}")
+    rng = np.random.default_rng(T * 7 + N)
+    xq = rng.integers(-128, 128, size=(T, K), dtype=np.int8)
+    packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+    s_vis, s_txt = 0.41, 0.013
+    acc_want = orc.gemm_i8_i4_i32(xq, orc.unpack_w4(packed))
+    ref, _ = orc.dequant(acc_want, V, s_vis, s_txt, w_scale)
+    wp = mq.w4_prepack(dev(packed))
+    acc = torch.full((T, N), -7, dtype=torch.int32, device="cuda")
+    ldy = N + 8
+    ybuf = torch.full((T, ldy), 9.0, dtype=torch.float16, device="cuda")
+    mq.w4a8_gemm(dev(xq), wp, dev(w_scale), N, V, s_vis, s_txt, out=ybuf[:, :N], acc_out=acc)
+    assert (acc.cpu().numpy() == acc_want).all()
+    yb = ybuf.cpu().numpy()
+    check_y(yb[:, :N], ref, "gemm small")
+    assert (yb[:, N:] == 9.0).all()                           # nothing written past N
+    # without acc_out the output is the same
+    y2 = mq.w4a8_gemm(dev(xq), wp, dev(w_scale), N, V, s_vis, s_txt).cpu().numpy()
+    assert (y2.view(np.uint16) == yb[:, :N].view(np.uint16)).all()
+
+
+def test_gemm_extreme_values_no_overflow(mq):
+    say("gemm extremes K=29568")
+    K, T, N = 29568, 64, 64
+    xq = np.full((T, K), -128, dtype=np.int8)
+    xq[1::2] = 127
+    packed = np.full((N, K // 2), 0x88, dtype=np.uint8)          # every weight -8
+    packed[1::2] = 0x77                                          # every weight +7
+    acc_want = orc.gemm_i8_i4_i32(xq, orc.unpack_w4(packed))
+    assert acc_want.max() == K * 1024
+    acc = torch.empty((T, N), dtype=torch.int32, device="cuda")
+    mq.w4a8_gemm(dev(xq), mq.w4_prepack(dev(packed)), dev(np.ones(N, dtype=np.float16)), N, 0,
+                 2.0 ** -20, 2.0 ** -20, acc_out=acc)
+    assert (acc.cpu().numpy() == acc_want).all()
+    # and the decode kernel on the same extremes
+    acc1 = torch.empty((2, N), dtype=torch.int32, device="cuda")
+    mq.w4a8_gemm(dev(xq[:2]), mq.w4_prepack(dev(packed)), dev(np.ones(N, dtype=np.float16)), N, 0,
+                 2.0 ** -20, 2.0 ** -20, acc_out=acc1)
+    assert (acc1.cpu().numpy() == acc_want[:2]).all()
+
+
+@pytest.mark.parametrize("T", [1, 2, 4, 16, 31, 32])
+def test_gemv_small_shapes_full(mq, T):
+    say(f"gemv T={T}")
+    rng = np.random.default_rng(T)
+    N, K, V = 200, 832, min(T, 3)
+    xq = rng.integers(-128, 128, size=(T, K), dtype=np.int8)
+    packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+    s_vis, s_txt = 0.2, 0.03
+    acc_want = orc.gemm_i8_i4_i32(xq, orc.unpack_w4(packed))
+    ref, _ = orc.dequant(acc_want, V, s_vis, s_txt, w_scale)
+    acc = torch.empty((T, N), dtype=torch.int32, device="cuda")
+    y = mq.w4a8_gemm(dev(xq), mq.w4_prepack(dev(packed)), dev(w_scale), N, V, s_vis, s_txt, acc_out=acc)
+    assert (acc.cpu().numpy() == acc_want).all()
+    check_y(y.cpu().numpy(), ref, f"gemv T={T}")
+
+
+def test_empty_inputs_are_noops(mq):
+    say("empty inputs")
+    e16 = torch.empty((0, 512), dtype=torch.float16, device="cuda")
+    assert mq.hadamard_quant_act(e16, 0, 1.0, 1.0, 512).shape == (0, 512)
+    assert mq.aifs_permute(e16, torch.empty(0, dtype=torch.int32, device="cuda")).shape == (0, 512)
+    wp = mq.w4_prepack(dev(np.zeros((32, 256), dtype=np.uint8)))
+    y = mq.w4a8_gemm(torch.empty((0, 512), dtype=torch.int8, device="cuda"), wp,
+                     dev(np.ones(32, dtype=np.float16)), 32, 0, 1.0, 1.0)
+    assert y.shape == (0, 32)
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------- full-size configurations
+
+def sample_rows(T, V, rng, n=48):
+    base = {0, 1, T - 1, T - 2, max(V - 1, 0), min(V, T - 1), min(V + 1, T - 1), max(V - 2, 0), 255, 256, 257}
+    base = {r for r in base if 0 <= r < T}
+    extra = rng.choice(T, size=min(n, T), replace=False).tolist()
+    return np.array(sorted(base | set(extra)), dtype=np.int64)
+
+
+def sample_cols(N, rng, n=192):
+    base = {0, 1, 31, 32, 255, 256, N - 1, N - 2, N - 32, N - 33}
+    base = {c for c in base if 0 <= c < N}
+    extra = rng.choice(N, size=min(n, N), replace=False).tolist()
+    return np.array(sorted(base | set(extra)), dtype=np.int64)
+
+
+def full_size_case(mq, cfg, proj, fused, T=None):
+    w = wl.workload(cfg, T)
+    inp = wl.make_linear_inputs(w, proj)
+    s_vis, s_txt = scales_from_calib(inp)
+    if not w.vis_spans:
+        s_vis = s_txt
+    say(f"cfg {cfg} {proj} T={inp['T']} K={inp['K']} N={inp['N']} fused={fused} s_vis={s_vis:.5g} s_txt={s_txt:.5g}")
+    rng = np.random.default_rng(cfg * 31 + inp["N"])
+    g = run_linear_gpu(mq, inp, s_vis, s_txt, want_acc=not fused, fused=fused)
+    rows = sample_rows(inp["T"], g["V"], rng)
+    cols = sample_cols(inp["N"], rng)
+    o = orc.w4a8_linear(inp["x"], inp["vis_spans"], inp["w_packed"], inp["w_scale"], s_vis, s_txt,
+                        w.had_block, rows=rows, cols=cols)
+    assert (g["perm"] == o["perm"]).all() and g["V"] == o["V"]
+    xq_gpu = g["xq"].cpu().numpy()
+    assert (xq_gpu == o["xq"]).all(), "int8 codes differ"
+    rd, cd = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
+    if not fused:
+        acc = g["acc"][rd][:, cd].cpu().numpy()
+        assert (acc == o["acc"]).all(), "int32 accumulators differ"
+    y = g["y"][rd][:, cd].cpu().numpy()
+    check_y(y, o["ref"], f"cfg{cfg} {proj}")
+    # whole-output property: every row got written with finite values of a plausible size
+    yf = g["y"].float()
+    assert torch.isfinite(yf).all()
+    assert float(yf.abs().max()) > 0
+    del g
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("proj", ["qkv", "o", "gate_up", "down"])
+def test_config1_prefill_T1280(mq, proj):
+    full_size_case(mq, 1, proj, fused=False)
+
+
+@pytest.mark.parametrize("proj", ["qkv", "o", "gate_up", "down"])
+def test_config2_prefill_T4096_fused(mq, proj):
+    full_size_case(mq, 2, proj, fused=True)
+
+
+def test_config2_unfused_down(mq):
+    full_size_case(mq, 2, "down", fused=False)
+
+
+@pytest.mark.parametrize("T", [1, 4, 16])
+def test_config3_decode_full(mq, T):
+    """Decode shapes are small enough for the oracle to compute every output."""
+    w = wl.workload(3, T)
+    for proj in w.projections:
+        inp = wl.make_linear_inputs(w, proj)
+        s_txt = float(orc.calibrate_static_scale(inp["calib_txt"], w.had_block))
+        say(f"cfg 3 {proj} T={T} K={inp['K']} N={inp['N']}")
+        o = orc.w4a8_linear(inp["x"], (), inp["w_packed"], inp["w_scale"], s_txt, s_txt, w.had_block)
+        g = run_linear_gpu(mq, inp, s_txt, s_txt)
+        assert g["V"] == 0
+        assert (g["xq"].cpu().numpy() == o["xq"]).all()
+        assert (g["acc"].cpu().numpy() == o["acc"]).all()
+        check_y(g["y"].cpu().numpy(), o["ref"], f"cfg3 {proj} T={T}")
+
+
+@pytest.mark.parametrize("proj", ["qkv", "o", "gate_up", "down"])
+def test_config4_72b_T16384(mq, proj):
+    full_size_case(mq, 4, proj, fused=(proj in ("gate_up", "down")))
