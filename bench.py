@@ -1,0 +1,278 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X W4A8 MSQ linear path (one GPU).
+
+A step is one pass of the whole hot path over one batch of the Qwen2-VL-7B
+shaped prefill workload (T = 1280 tokens, 1024 visual in one span): the AIFS
+mask remap and the standalone row permute of the [T, 3584] embeddings once,
+then for each of the four decoder-layer linears (qkv, o, gate_up, down) the
+block-Hadamard rotation + modality-specific static int8 quantization (with the
+AIFS gather fused in) and the int4 x int8 GEMM with the fused dequant epilogue.
+Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is prefill int8 TOPS = 2*T*sum(K*N) / step time.
+`roofline` covers the dominant kernel (the MFMA GEMM), its duration measured
+with HIP events inside the timed steps.  `decode` reports the weight-streaming
+GEMV (T in {1,4,16}) over 28 distinct layers of weights (3.1 GB, more than the
+256 MB last-level cache) in GB/s.  `cpu_baseline` times the CPU oracle on a
+bounded row sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "W4A8 linear throughput: prefill int8 TOPS (% MFMA peak); decode GB/s (% HBM)"
+INT8_MFMA_PEAK_TOPS = 5000.0       # MI355X dense int8, published
+HBM_PEAK_GBPS = 8000.0             # MI355X HBM3E, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--decode-layers", type=int, default=28)
+    ap.add_argument("--decode-iters", type=int, default=5)
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=512,
+                    help="rows of the prefill workload the CPU oracle is timed on")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path shards by rows / output channels, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    import paper_2502_00425_amd as pkg
+    from paper_2502_00425_amd import binding as mq       # raises if libmquant.so is missing
+    from paper_2502_00425_amd import workloads as wl
+
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    # ------------------------------------------------------------ prefill set-up
+    w = wl.workload(1)
+    T, B = w.T, w.had_block
+    perm, inv, V = mq.aifs_build_perm(T, w.vis_spans)
+    permd = dev(perm)
+    mask = torch.tril(torch.ones((T, T), dtype=torch.uint8, device="cuda"))
+    mask_u = torch.empty_like(mask)
+    lin = {}
+    for proj, (K, N) in w.projections.items():
+        inp = wl.make_linear_inputs(w, proj)
+        absmax = torch.zeros(2, dtype=torch.float32, device="cuda")
+        mq.hadamard_absmax(dev(inp["calib_vis"]), B, absmax[0:1])
+        mq.hadamard_absmax(dev(inp["calib_txt"]), B, absmax[1:2])
+        a = absmax.cpu().numpy()
+        lin[proj] = {
+            "K": K, "N": N, "x": dev(inp["x"]),
+            "wp": mq.w4_prepack(dev(inp["w_packed"])), "w_scale": dev(inp["w_scale"]),
+            "s_vis": pkg.static_scale_from_absmax(a[0], B),
+            "s_txt": pkg.static_scale_from_absmax(a[1], B),
+            "xq": torch.empty((T, K), dtype=torch.int8, device="cuda"),
+            "y": torch.empty((T, N), dtype=torch.float16, device="cuda"),
+            "host": inp,
+        }
+        nws = mq.w4a8_workspace_bytes(T, N, K)
+        lin[proj]["ws"] = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+    x_embed = lin["qkv"]["x"]
+    x_u = torch.empty_like(x_embed)
+    gemm_ops = sum(2.0 * T * l["K"] * l["N"] for l in lin.values())
+
+    ev_pairs = []      # (proj, start, end) around every GEMM launch of the timed steps
+
+    def step(record: bool):
+        mq.aifs_remap_mask(mask, permd, out=mask_u)
+        mq.aifs_permute(x_embed, permd, out=x_u)
+        for proj, l in lin.items():
+            mq.hadamard_quant_act(l["x"], V, l["s_vis"], l["s_txt"], B, perm_dev=permd, out=l["xq"])
+            if record:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            mq.w4a8_gemm(l["xq"], l["wp"], l["w_scale"], l["N"], V, l["s_vis"], l["s_txt"],
+                         out=l["y"], workspace=l["ws"])
+            if record:
+                e1.record()
+                ev_pairs.append((proj, e0, e1))
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tops = gemm_ops / (ms_per_step * 1e-3) / 1e12
+
+    per_proj_ms = {p: 0.0 for p in lin}
+    for proj, e0, e1 in ev_pairs:
+        per_proj_ms[proj] += e0.elapsed_time(e1)
+    for p in per_proj_ms:
+        per_proj_ms[p] /= args.steps
+    gemm_ms = sum(per_proj_ms.values())
+    n_launch = len(lin)
+    gemm_tops = gemm_ops / (gemm_ms * 1e-3) / 1e12
+    breakdown = {p: {"gemm_us": round(per_proj_ms[p] * 1e3, 2),
+                     "tops": round(2.0 * T * lin[p]["K"] * lin[p]["N"] / (per_proj_ms[p] * 1e-3) / 1e12, 1)}
+                 for p in lin}
+
+    # front-end (rotate + quant) timed on its own, for the record
+    fe_bytes = sum(3.0 * T * l["K"] for l in lin.values())
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    e0.record()
+    for _ in range(reps):
+        for proj, l in lin.items():
+            mq.hadamard_quant_act(l["x"], V, l["s_vis"], l["s_txt"], B, perm_dev=permd, out=l["xq"])
+    e1.record()
+    torch.cuda.synchronize()
+    fe_ms = e0.elapsed_time(e1) / reps
+
+    result = {
+        "metric": METRIC, "value": round(tops, 2), "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8 x int4 -> int32 (fp16 in/out)", "data": "synthetic",
+        "config": {"workload": "configs[1]: Qwen2-VL-7B-shaped prefill, T=1280 (1024 visual at 16), "
+                               "qkv 3584x4608, o 3584x3584, gate_up 3584x37888, down 18944x3584, "
+                               "block-Hadamard 512",
+                   "T": T, "n_vis": V, "had_block": B},
+        "roofline": {
+            "bound": "mfma", "kernel": "w4a8_gemm_kernel",
+            "achieved": round(gemm_tops / 1e3, 4), "peak": INT8_MFMA_PEAK_TOPS / 1e3,
+            "unit": "POP/s (int8; = 1000 TOPS)", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
+            "traffic": None,
+            "avg_launch_us": round(gemm_ms * 1e3 / n_launch, 2),
+            "ops_per_launch_avg": gemm_ops / n_launch,
+            "per_projection": breakdown,
+        },
+        "front_end": {"kernel": "hadamard_quant_kernel", "bound": "hbm",
+                      "us_per_step": round(fe_ms * 1e3, 2),
+                      "GBps": round(fe_bytes / (fe_ms * 1e-3) / 1e9, 1),
+                      "frac": round(fe_bytes / (fe_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+    }
+
+    # ------------------------------------------------------------------ decode
+    if not args.no_decode:
+        result["decode"] = bench_decode(args, torch, mq, wl)
+
+    # ------------------------------------------------------------ CPU baseline
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args, np, w, lin, V)
+
+    print(json.dumps(result), flush=True)
+
+
+def bench_decode(args, torch, mq, wl):
+    """GEMV over `decode_layers` distinct layers of 7B weights (uniform random
+    int4 nibbles written directly in the streamed layout; the contents do not
+    change the traffic) for T in {1, 4, 16}, text rows only."""
+    out = {"unit": "GB/s", "peak": HBM_PEAK_GBPS, "layers": args.decode_layers, "per_T": {}}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3000)
+    wd = wl.workload(3, 1)
+    layers = []
+    for _ in range(args.decode_layers):
+        layer = {}
+        for proj, (K, N) in wd.projections.items():
+            nbytes = mq.w4_prepacked_bytes(N, K)
+            wp = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda", generator=gen)
+            ws = (torch.rand(N, device="cuda", generator=gen) * 0.015 + 0.005).half()
+            layer[proj] = (K, N, wp, ws)
+        layers.append(layer)
+    for T in (1, 4, 16):
+        xs = {K: torch.randn((T, K), device="cuda", generator=gen).half() for K in (3584, 18944)}
+        xq = {K: torch.empty((T, K), dtype=torch.int8, device="cuda") for K in xs}
+        ys = {N: torch.empty((T, N), dtype=torch.float16, device="cuda") for N in (3584, 512, 18944)}
+        s_txt = 0.035
+
+        def one_pass():
+            for layer in layers:
+                for proj, (K, N, wp, ws) in layer.items():
+                    mq.hadamard_quant_act(xs[K], 0, s_txt, s_txt, 512, out=xq[K])
+                    mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
+
+        def gemv_only_pass():
+            for layer in layers:
+                for proj, (K, N, wp, ws) in layer.items():
+                    mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
+
+        bytes_layer = sum(K * N / 2 + 2 * N + T * K + 2 * T * N for (K, N) in wd.projections.values())
+        res = {}
+        for name, fn in (("quant+gemv", one_pass), ("gemv_only", gemv_only_pass)):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.decode_iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms_layer = e0.elapsed_time(e1) / args.decode_iters / len(layers)
+            gbps = bytes_layer / (ms_layer * 1e-3) / 1e9
+            res[name] = {"us_per_layer": round(ms_layer * 1e3, 2), "GBps": round(gbps, 1),
+                         "frac": round(gbps / HBM_PEAK_GBPS, 4)}
+        res["bytes_per_layer"] = bytes_layer
+        out["per_T"][f"T{T}"] = res
+    return out
+
+
+def cpu_baseline(args, np, w, lin, V):
+    """The oracle as it stands, on a row sample of the prefill workload: the
+    first cpu_rows/2 visual rows and the first cpu_rows/2 text rows (AIFS
+    order) through all four projections, all output channels."""
+    from oracle import mquant_oracle as orc
+    half = max(args.cpu_rows // 2, 1)
+    rows = np.r_[np.arange(0, half), np.arange(V, V + half)]
+    ops = 0.0
+    t_total = 0.0
+    stages = {"permute": 0.0, "rotate_quant": 0.0, "unpack": 0.0, "gemm": 0.0, "dequant": 0.0}
+    for proj, l in lin.items():
+        inp = l["host"]
+        t = time.perf_counter()
+        perm, _, V2 = orc.aifs_build_perm(inp["T"], inp["vis_spans"])
+        x_u = orc.aifs_permute_rows(inp["x"], perm)[rows]
+        stages["permute"] += time.perf_counter() - t
+        t = time.perf_counter()
+        xq = orc.msq_quantize(orc.hadamard_rotate(x_u, w.had_block), half, l["s_vis"], l["s_txt"], w.had_block)
+        stages["rotate_quant"] += time.perf_counter() - t
+        t = time.perf_counter()
+        wq = orc.unpack_w4(inp["w_packed"])
+        stages["unpack"] += time.perf_counter() - t
+        t = time.perf_counter()
+        acc = orc.gemm_i8_i4_i32(xq, wq)
+        stages["gemm"] += time.perf_counter() - t
+        t = time.perf_counter()
+        orc.dequant(acc, half, l["s_vis"], l["s_txt"], inp["w_scale"])
+        stages["dequant"] += time.perf_counter() - t
+        ops += 2.0 * len(rows) * l["K"] * l["N"]
+    t_total = sum(stages.values())
+    return {"value": round(ops / t_total / 1e12, 5), "unit": "TOPS", "cores": orc.num_threads(),
+            "kind": "oracle",
+            "sample": f"{len(rows)} of {w.T} rows ({half} visual + {half} text) x all channels of the "
+                      f"four projections; {round(t_total, 2)} s wall",
+            "seconds": round(t_total, 3),
+            "stage_seconds": {k: round(v, 3) for k, v in stages.items()}}
+
+
+if __name__ == "__main__":
+    main()
