@@ -104,46 +104,92 @@ __device__ __forceinline__ void store_out(int32_t acc16, int32_t row, int32_t n,
 }
 
 // ------------------------------------------------------------------- GEMM
+//
+// Work-group tile BM x BN, 8 wavefronts (WM x WN), two per SIMD so that one
+// wave's LDS reads and unpack hide under the other's MFMAs.  K advances in
+// stages of 128 channels.  A stage is copied HBM/L2 -> LDS by LDS-DMA loads
+// (global_load_lds_dwordx4: 16 bytes per lane, no VGPR staging), three stages
+// deep:
+//   A (activations): BM rows x 128 bytes; the eight 16-byte chunks of a row are
+//     XOR-swizzled with (row & 7), so the DMA writes (8 lanes per row) and the
+//     MFMA fragment reads (32 lanes down a column of chunks) are both free of
+//     bank conflicts.  The swizzle is applied on the global side: lane i of a
+//     1 KiB DMA chunk always lands at LDS offset 16 * i.
+//   B (weights): BN/32 n-tiles x 2 k-tiles x 1 KiB, a straight copy of the
+//     prepacked tiles; a fragment read is lane * 16, conflict free.
+// The DMA loads are issued through inline asm and tracked with explicit
+// s_waitcnt vmcnt(n): the compiler would otherwise wait for every outstanding
+// LDS-DMA before each ds_read and serialise the pipeline.
 
-// LDS image of one A stage: BM rows x 128 bytes, the eight 16-byte chunks of a
-// row XOR-swizzled with (row & 7) so that both the row-wise writes and the
-// column-wise MFMA fragment reads are bank-conflict free.
+typedef const void __attribute__((address_space(1))) *global_ptr_t;
+typedef void __attribute__((address_space(3))) *lds_ptr_t;
+
+// 16 bytes per lane, global -> LDS; LDS address = wave-uniform base + lane * 16.
+__device__ __forceinline__ void lds_dma16(const uint8_t *gsrc, uint8_t *lds_wave_base)
+{
+    const uint32_t m0v =
+        __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+            (lds_ptr_t)lds_wave_base)));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(m0v), "v"(gsrc)
+                 : "memory", "m0");
+}
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits [3:0] and [15:14]).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
 __device__ __forceinline__ int lds_a_offset(int row, int chunk)
 {
     return row * 128 + ((chunk ^ (row & 7)) << 4);
 }
 
-template <int BM, int BN, int WM, int WN>
+// Work-group id -> (tm, tn).  Work-groups are dealt round-robin to the 8 XCDs,
+// each with its own L2: XCD x gets a contiguous run of the tile order, and the
+// order walks bands of BAND tile-rows, so the ~32 tiles an XCD runs at a time
+// form a compact block that shares few A row-panels and few B column-panels.
+template <int BAND>
+__device__ __forceinline__ void tile_of_group(int32_t id, int32_t tiles_m, int32_t tiles_n,
+                                              int32_t &tm, int32_t &tn)
+{
+    const int32_t total = tiles_m * tiles_n;
+    const int32_t per = total / 8, rem = total % 8;
+    const int32_t xcd = id % 8, local = id / 8;
+    const int32_t t = xcd * per + (xcd < rem ? xcd : rem) + local;
+    const int32_t band_tiles = BAND * tiles_n;
+    const int32_t band = t / band_tiles;
+    const int32_t in_band = t - band * band_tiles;
+    const int32_t rows = (tiles_m - band * BAND) < BAND ? (tiles_m - band * BAND) : BAND;
+    tm = band * BAND + in_band % rows;
+    tn = in_band / rows;
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, int BAND>
 __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
     const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
     __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
     int32_t K, int32_t n_vis, float s_vis, float s_txt, int32_t tiles_m, int32_t tiles_n,
     int32_t n_tiles32)
 {
-    constexpr int THREADS = WM * WN * 64;
+    constexpr int NW = WM * WN;
     constexpr int MT = BM / WM / 32;          // 32x32 tiles per wave along M
     constexpr int NT = BN / WN / 32;          // ... along N
-    constexpr int A_STAGE = BM * 128;         // bytes
-    constexpr int A_CHUNKS = BM * 8 / THREADS;
+    constexpr int A_STAGE = BM * 128, B_STAGE = BN * 64, STAGE = A_STAGE + B_STAGE;
+    constexpr int A_CH = BM / 8, B_CH = BN / 16;      // 1 KiB DMA chunks per stage
+    constexpr int CH = (A_CH + B_CH) / NW;            // ... per wave
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "tile shape");
-    static_assert((BM * 8) % THREADS == 0, "A copy shape");
+    static_assert((A_CH + B_CH) % NW == 0, "chunks must divide evenly over the waves");
+    static_assert(STAGES >= 2 && CH * (STAGES - 2) < 64, "pipeline depth");
 
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
-    // Tile assignment: consecutive work-group ids are dealt round-robin to the
-    // 8 XCDs, so group ids that share (id % 8) run on one XCD and share its L2.
-    // Give each XCD a contiguous run of tiles; inside a run M varies fastest so
-    // the tiles that reuse one weight panel are neighbours.
-    const int32_t total = tiles_m * tiles_n;
-    int32_t tile = blockIdx.x;
-    {
-        const int32_t per = total / 8, rem = total % 8;
-        const int32_t xcd = tile % 8, local = tile / 8;
-        // XCD x owns per + (x < rem) tiles
-        tile = xcd * per + (xcd < rem ? xcd : rem) + local;
-    }
-    const int32_t tm = tile % tiles_m;
-    const int32_t tn = tile / tiles_m;
+    int32_t tm, tn;
+    tile_of_group<BAND>(blockIdx.x, tiles_m, tiles_n, tm, tn);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -156,6 +202,7 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
     const int32_t row0 = tm * BM;
     const int32_t k_tiles = K / kPackK;
     const int32_t k_blocks = K / 128;         // K % 128 == 0 is guaranteed by the host
+    const int32_t ntile0 = tn * (BN / 32);
 
     v16i acc[MT][NT];
 #pragma unroll
@@ -165,99 +212,91 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0;
 
-    // ---- A: global -> registers -> LDS
-    uint4 a_stage[A_CHUNKS];
-    auto load_a = [&](int32_t kb) {
+    // Per-lane global source of each DMA chunk this wave copies, for k-block 0.
+    // Rows past T and n-tiles past the padded N are clamped to valid memory; the
+    // values they produce are never stored.
+    const uint8_t *src[CH];
+    int32_t src_step[CH];
 #pragma unroll
-        for (int it = 0; it < A_CHUNKS; ++it) {
-            const int q = it * THREADS + tid;
-            const int r = q >> 3, c = q & 7;
-            const int32_t row = row0 + r;
-            if (row < T) {
-                a_stage[it] = *reinterpret_cast<const uint4 *>(
-                    xq + static_cast<int64_t>(row) * K + static_cast<int64_t>(kb) * 128 + c * 16);
-            } else {
-                a_stage[it] = make_uint4(0, 0, 0, 0);
-            }
+    for (int j = 0; j < CH; ++j) {
+        const int q = wave + j * NW;
+        if (q < A_CH) {
+            const int r = q * 8 + (lane >> 3);
+            const int logical = (lane & 7) ^ (r & 7);
+            int32_t row = row0 + r;
+            row = row < T ? row : T - 1;
+            src[j] = reinterpret_cast<const uint8_t *>(xq) + static_cast<int64_t>(row) * K +
+                     logical * 16;
+            src_step[j] = 128;
+        } else {
+            const int b = q - A_CH, nt = b >> 1, ks = b & 1;
+            int32_t ntile = ntile0 + nt;
+            ntile = ntile < n_tiles32 ? ntile : n_tiles32 - 1;
+            src[j] = reinterpret_cast<const uint8_t *>(wp) +
+                     ((static_cast<int64_t>(ntile) * k_tiles + ks) * 64 + lane) * 16;
+            src_step[j] = 2 * kPackTileBytes;
         }
+    }
+    auto load_stage = [&](int32_t kb, int buf) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j)
+            lds_dma16(src[j] + static_cast<int64_t>(kb) * src_step[j],
+                      smem + buf * STAGE + (wave + j * NW) * 1024);
     };
-    auto store_a = [&](int buf) {
-#pragma unroll
-        for (int it = 0; it < A_CHUNKS; ++it) {
-            const int q = it * THREADS + tid;
-            const int r = q >> 3, c = q & 7;
-            *reinterpret_cast<uint4 *>(smem + buf * A_STAGE + lds_a_offset(r, c)) = a_stage[it];
-        }
-    };
-
-    // ---- B: global -> registers, one k-block (two k-tiles) ahead
-    const int32_t nt0 = (tn * BN + wn * (BN / WN)) / 32;       // first 32-channel tile of this wave
-    uint4 b_next[2][NT];
-    auto load_b = [&](int32_t kb) {
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const int32_t ntile = nt0 + nt;
-                if (ntile < n_tiles32) {
-                    b_next[ks][nt] =
-                        wp[(static_cast<int64_t>(ntile) * k_tiles + (kb * 2 + ks)) * 64 + lane];
-                } else {
-                    b_next[ks][nt] = make_uint4(0, 0, 0, 0);
-                }
-            }
-    };
-
-    load_a(0);
-    load_b(0);
-    store_a(0);
-    __syncthreads();
-
-    for (int32_t kb = 0; kb < k_blocks; ++kb) {
-        const int buf = kb & 1;
-        uint4 b_cur[2][NT];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) b_cur[ks][nt] = b_next[ks][nt];
-        if (kb + 1 < k_blocks) {
-            load_a(kb + 1);
-            load_b(kb + 1);
-        }
-
-        const uint8_t *abase = smem + buf * A_STAGE;
+    auto compute = [&](int buf) {
+        const uint8_t *abase = smem + buf * STAGE;
+        const uint8_t *bbase = abase + A_STAGE;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            v4i a0[MT], a1[MT];
+            v4i a[MT][2], b[NT][2];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const int r = wm * (BM / WM) + mt * 32 + l32;
                 const int c = ks * 4 + g * 2;
-                a0[mt] = as_v4i(*reinterpret_cast<const uint4 *>(abase + lds_a_offset(r, c)));
-                a1[mt] = as_v4i(*reinterpret_cast<const uint4 *>(abase + lds_a_offset(r, c + 1)));
+                a[mt][0] = as_v4i(*reinterpret_cast<const uint4 *>(abase + lds_a_offset(r, c)));
+                a[mt][1] = as_v4i(*reinterpret_cast<const uint4 *>(abase + lds_a_offset(r, c + 1)));
             }
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                v4i b0, b1;
-                unpack_w4x16(b_cur[ks][nt], b0, b1);
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    acc[mt][nt] =
-                        __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[mt], b0, acc[mt][nt], 0, 0, 0);
-                    acc[mt][nt] =
-                        __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[mt], b1, acc[mt][nt], 0, 0, 0);
-                }
+                const uint4 p = *reinterpret_cast<const uint4 *>(
+                    bbase + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
+                unpack_w4x16(p, b[nt][0], b[nt][1]);
             }
+            // consecutive MFMAs write different accumulators (a dependent pair
+            // back to back would wait out the full MFMA latency)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                            a[mt][h], b[nt][h], acc[mt][nt], 0, 0, 0);
         }
+    };
 
-        if (kb + 1 < k_blocks) store_a(buf ^ 1);
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < k_blocks) load_stage(s, s);
+
+    int buf = 0, nbuf = STAGES - 1;
+    for (int32_t kb = 0; kb < k_blocks; ++kb) {
+        // Stage kb must have landed; the STAGES-2 younger stages may stay in flight.
+        if (kb + STAGES - 2 < k_blocks) wait_vmcnt<CH * (STAGES - 2)>();
+        else wait_vmcnt<0>();
+        // After the barrier every wave sees stage kb and has finished reading
+        // stage kb-1, whose buffer the next DMA overwrites.
         __syncthreads();
+        if (kb + STAGES - 1 < k_blocks) load_stage(kb + STAGES - 1, nbuf);
+        compute(buf);
+        buf = buf + 1 == STAGES ? 0 : buf + 1;
+        nbuf = nbuf + 1 == STAGES ? 0 : nbuf + 1;
     }
 
     // ---- epilogue: scale select by row span, per-channel scale, fp16 store
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int32_t n = (nt0 + nt) * 32 + l32;
+        const int32_t n = (ntile0 + wn * NT + nt) * 32 + l32;
         if (n >= N) continue;
         const float ws = __half2float(w_scale[n]);
 #pragma unroll
@@ -373,7 +412,7 @@ int check_gemm_args(const void *xq, const void *wp, const void *w_scale, const v
     return MQUANT_OK;
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int STAGES, int BAND>
 int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y, int64_t ldy,
                 int32_t *acc_out, int32_t T, int32_t N, int32_t K, int32_t n_vis, float s_vis,
                 float s_txt, hipStream_t stream)
@@ -381,8 +420,8 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
     const int32_t tiles_m = static_cast<int32_t>(ceil_div(T, BM));
     const int32_t tiles_n = static_cast<int32_t>(ceil_div(N, BN));
     const int32_t n_tiles32 = static_cast<int32_t>(ceil_div(N, kPackN));
-    const size_t lds = 2 * BM * 128;
-    auto kern = w4a8_gemm_kernel<BM, BN, WM, WN>;
+    const size_t lds = static_cast<size_t>(STAGES) * (BM * 128 + BN * 64);
+    auto kern = w4a8_gemm_kernel<BM, BN, WM, WN, STAGES, BAND>;
     static bool attr_set = false;       // raising the dynamic LDS limit is idempotent
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -396,6 +435,22 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
                        static_cast<__half *>(y), ldy, acc_out, T, N, K, n_vis, s_vis, s_txt,
                        tiles_m, tiles_n, n_tiles32);
     return launch_status();
+}
+
+// Tile choice.  256x256 (one work-group per CU, three stages) has the best
+// steady-state rate; 128x256 with two stages fits two work-groups per CU, which
+// hides one group's prologue and epilogue under the other's main loop and
+// halves the tile-count granularity.  Cost model: rounds over the 256 CUs times
+// tile area, the smaller tile derated by its measured relative rate.
+constexpr int kNumCU = 256;
+
+int pick_gemm_tile(int32_t T, int32_t N)
+{
+    const double a = static_cast<double>(ceil_div(ceil_div(T, 256) * ceil_div(N, 256), kNumCU)) *
+                     256.0 * 256.0;
+    const double b = static_cast<double>(ceil_div(ceil_div(T, 128) * ceil_div(N, 256), kNumCU)) *
+                     128.0 * 256.0 / 0.93;
+    return a <= b ? 0 : 1;
 }
 
 }  // namespace
@@ -464,8 +519,11 @@ extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void 
         }
         return MQUANT_OK;
     }
-    return launch_gemm<256, 256, 2, 2>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis, s_vis,
-                                       s_txt, stream);
+    if (pick_gemm_tile(T, N) == 0)
+        return launch_gemm<256, 256, 2, 4, 3, 4>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
+                                                 s_vis, s_txt, stream);
+    return launch_gemm<128, 256, 2, 4, 2, 8>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
+                                             s_vis, s_txt, stream);
 }
 
 extern "C" int64_t mquant_w4a8_linear_prefill_workspace_bytes(int32_t T, int32_t N, int32_t K)
