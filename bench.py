@@ -189,6 +189,7 @@ def bench_decode(args, torch, mq, wl):
     out = {"unit": "GB/s", "peak": HBM_PEAK_GBPS, "layers": args.decode_layers, "per_T": {}}
     gen = torch.Generator(device="cuda")
     gen.manual_seed(3000)
+    streams = [torch.cuda.Stream() for _ in range(4)]
     wd = wl.workload(3, 1)
     layers = []
     for _ in range(args.decode_layers):
@@ -203,6 +204,8 @@ def bench_decode(args, torch, mq, wl):
         xs = {K: torch.randn((T, K), device="cuda", generator=gen).half() for K in (3584, 18944)}
         xq = {K: torch.empty((T, K), dtype=torch.int8, device="cuda") for K in xs}
         ys = {N: torch.empty((T, N), dtype=torch.float16, device="cuda") for N in (3584, 512, 18944)}
+        ys_multi = [{N: torch.empty((T, N), dtype=torch.float16, device="cuda") for N in (3584, 512, 18944)}
+                    for _ in range(8)]
         s_txt = 0.035
 
         def one_pass():
@@ -216,18 +219,27 @@ def bench_decode(args, torch, mq, wl):
                 for proj, (K, N, wp, ws) in layer.items():
                     mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
 
+        def gemv_streams_pass():
+            # the seven GEMVs of a layer are independent launches here (each has its own
+            # input and output), so they may overlap: round-robin over four streams
+            i = 0
+            for layer in layers:
+                for proj, (K, N, wp, ws) in layer.items():
+                    with torch.cuda.stream(streams[i & 3]):
+                        mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys_multi[i % len(ys_multi)][N])
+                    i += 1
+
         bytes_layer = sum(K * N / 2 + 2 * N + T * K + 2 * T * N for (K, N) in wd.projections.values())
         res = {}
-        for name, fn in (("quant+gemv", one_pass), ("gemv_only", gemv_only_pass)):
+        for name, fn in (("quant+gemv", one_pass), ("gemv_only", gemv_only_pass),
+                         ("gemv_only_4streams", gemv_streams_pass)):
             fn()
             torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
+            t0 = time.perf_counter()
             for _ in range(args.decode_iters):
                 fn()
-            e1.record()
             torch.cuda.synchronize()
-            ms_layer = e0.elapsed_time(e1) / args.decode_iters / len(layers)
+            ms_layer = (time.perf_counter() - t0) * 1e3 / args.decode_iters / len(layers)
             gbps = bytes_layer / (ms_layer * 1e-3) / 1e9
             res[name] = {"us_per_layer": round(ms_layer * 1e3, 2), "GBps": round(gbps, 1),
                          "frac": round(gbps / HBM_PEAK_GBPS, 4)}

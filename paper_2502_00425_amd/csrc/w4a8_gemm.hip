@@ -316,15 +316,20 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
 // ------------------------------------------------------------------- GEMV
 
 // Decode shape (T <= 32): the weights are streamed once from HBM and nothing
-// is reused, so there is no LDS staging.  One work-group owns one 32-channel
-// tile; its waves split K and the partial accumulators meet in LDS.
-template <int NWAVES>
+// is reused, so there is no LDS staging of operands.  One work-group owns one
+// 32-channel tile; its NWAVES waves split K, and every wave requests a whole
+// batch of KT k-tiles (activations first, they hit L2; then the weights, with
+// the non-temporal hint) before it touches the first one.  Loads are branch
+// free: addresses past a wave's K range are clamped and the weights masked to
+// zero, and lanes whose token row is >= T read row T-1 (rows >= T of the MFMA
+// result are never stored).  The partial sums of the waves meet in LDS.
+template <int NWAVES, int KT>
 __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
     const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
     __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
     int32_t K, int32_t n_vis, float s_vis, float s_txt)
 {
-    constexpr int UNROLL = 4;
+    typedef unsigned int v4u __attribute__((ext_vector_type(4)));
     __shared__ int32_t red[NWAVES][16][64];
 
     const int lane = threadIdx.x & 63;
@@ -333,57 +338,74 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
     const int g = lane >> 5;
     const int32_t ntile = blockIdx.x;
     const int32_t k_tiles = K / kPackK;
+    const int32_t per_wave = (k_tiles + NWAVES - 1) / NWAVES;
+    const int32_t kt_begin = wave * per_wave;
+    int32_t kt_end = kt_begin + per_wave;
+    kt_end = kt_end < k_tiles ? kt_end : k_tiles;
+    const int32_t n = ntile * 32 + l32;
+    const __half ws_h = w_scale[n < N ? n : N - 1];      // requested early, used in the epilogue
 
-    v16i acc;
+    v16i acc0, acc1;                                      // two chains: no back-to-back dependent MFMAs
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0;
-
+    for (int r = 0; r < 16; ++r) {
+        acc0[r] = 0;
+        acc1[r] = 0;
+    }
     const uint4 *wtile = wp + static_cast<int64_t>(ntile) * k_tiles * 64 + lane;
-    const bool row_ok = l32 < T;
-    const int8_t *xrow = xq + static_cast<int64_t>(row_ok ? l32 : 0) * K + g * 32;
+    const int8_t *xrow = xq + static_cast<int64_t>(l32 < T ? l32 : T - 1) * K + g * 32;
 
-    for (int32_t kt0 = wave * UNROLL; kt0 < k_tiles; kt0 += NWAVES * UNROLL) {
-        uint4 b[UNROLL], a0[UNROLL], a1[UNROLL];
+    for (int32_t base = kt_begin; base < kt_end; base += KT) {
+        uint4 a0[KT], a1[KT], b[KT];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int32_t kt = kt0 + u;
-            if (kt < k_tiles) {
-                b[u] = wtile[static_cast<int64_t>(kt) * 64];
-                if (row_ok) {
-                    a0[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64);
-                    a1[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64 + 16);
-                } else {
-                    a0[u] = make_uint4(0, 0, 0, 0);
-                    a1[u] = make_uint4(0, 0, 0, 0);
-                }
-            } else {
-                b[u] = make_uint4(0, 0, 0, 0);
-                a0[u] = make_uint4(0, 0, 0, 0);
-                a1[u] = make_uint4(0, 0, 0, 0);
-            }
+        for (int u = 0; u < KT; ++u) {
+            int32_t kt = base + u;
+            kt = kt < kt_end ? kt : kt_end - 1;
+            a0[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64);
+            a1[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64 + 16);
         }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
+        for (int u = 0; u < KT; ++u) {
+            int32_t kt = base + u;
+            kt = kt < kt_end ? kt : kt_end - 1;
+            const v4u t = __builtin_nontemporal_load(
+                reinterpret_cast<const v4u *>(wtile + static_cast<int64_t>(kt) * 64));
+            b[u] = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+#pragma unroll
+        for (int u = 0; u < KT; ++u) {
+            const uint32_t m = (base + u < kt_end) ? 0xFFFFFFFFu : 0u;     // wave-uniform
+            uint4 bb = b[u];
+            bb.x &= m;
+            bb.y &= m;
+            bb.z &= m;
+            bb.w &= m;
             v4i b0, b1;
-            unpack_w4x16(b[u], b0, b1);
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a0[u]), b0, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a1[u]), b1, acc, 0, 0, 0);
+            unpack_w4x16(bb, b0, b1);
+            acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a0[u]), b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a1[u]), b1, acc1, 0, 0, 0);
         }
+        // Scheduling order inside a batch: all 3*KT memory reads first, then the
+        // arithmetic.  Without this the scheduler sinks each load next to its use
+        // and the wave waits out one memory round trip per k-tile.
+        __builtin_amdgcn_sched_group_barrier(0x020, 3 * KT, 0);
+        __builtin_amdgcn_sched_group_barrier(0x00A, 18 * KT, 0);
     }
 
+    // Accumulator register r of k-group g holds row acc_row(r, g): with T <= 8
+    // only r < 4 can be a valid row, with T <= 16 only r < 8.
+    const int rmax = T <= 8 ? 4 : (T <= 16 ? 8 : 16);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r];
+    for (int r = 0; r < 16; ++r)
+        if (r < rmax) red[wave][r][lane] = acc0[r] + acc1[r];
     __syncthreads();
 
-    // Each wave finishes a quarter of the accumulator registers.
-    const int32_t n = ntile * 32 + l32;
-    const float ws = n < N ? __half2float(w_scale[n]) : 0.0f;
-    for (int r = wave; r < 16; r += NWAVES) {
-        int32_t sum = 0;
-#pragma unroll
-        for (int w = 0; w < NWAVES; ++w) sum += red[w][r][lane];
+    const float ws = __half2float(ws_h);
+    for (int r = wave; r < rmax; r += NWAVES) {
         const int32_t row = acc_row(r, g);
         if (row < T && n < N) {
+            int32_t sum = 0;
+#pragma unroll
+            for (int w = 0; w < NWAVES; ++w) sum += red[w][r][lane];
             const float s_row = row < n_vis ? s_vis : s_txt;
             store_out(sum, row, n, s_row, ws, y, ldy, acc_out, N);
         }
@@ -507,13 +529,21 @@ extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void 
             const int32_t tt = T - t0 < kGemvMaxT ? T - t0 : kGemvMaxT;
             int32_t nv = n_vis - t0;
             nv = nv < 0 ? 0 : (nv > tt ? tt : nv);
-            hipLaunchKernelGGL((w4a8_gemv_kernel<4>), dim3(static_cast<unsigned>(ceil_div(N, 32))),
-                               dim3(256), 0, stream, xq + static_cast<int64_t>(t0) * K,
-                               reinterpret_cast<const uint4 *>(wp),
-                               static_cast<const __half *>(w_scale),
-                               static_cast<__half *>(y) + static_cast<int64_t>(t0) * ldy, ldy,
-                               acc_out ? acc_out + static_cast<int64_t>(t0) * N : nullptr, tt, N, K,
-                               nv, s_vis, s_txt);
+            const unsigned n_tiles = static_cast<unsigned>(ceil_div(N, 32));
+            const int8_t *xs = xq + static_cast<int64_t>(t0) * K;
+            __half *ys = static_cast<__half *>(y) + static_cast<int64_t>(t0) * ldy;
+            int32_t *as = acc_out ? acc_out + static_cast<int64_t>(t0) * N : nullptr;
+            // Few n-tiles: more waves per tile to keep enough loads in flight.
+            if (n_tiles >= 256)
+                hipLaunchKernelGGL((w4a8_gemv_kernel<8, 4>), dim3(n_tiles), dim3(512), 0, stream, xs,
+                                   reinterpret_cast<const uint4 *>(wp),
+                                   static_cast<const __half *>(w_scale), ys, ldy, as, tt, N, K, nv,
+                                   s_vis, s_txt);
+            else
+                hipLaunchKernelGGL((w4a8_gemv_kernel<16, 4>), dim3(n_tiles), dim3(1024), 0, stream,
+                                   xs, reinterpret_cast<const uint4 *>(wp),
+                                   static_cast<const __half *>(w_scale), ys, ldy, as, tt, N, K, nv,
+                                   s_vis, s_txt);
             const int ls = launch_status();
             if (ls != MQUANT_OK) return ls;
         }
