@@ -29,6 +29,11 @@ if ROOT not in sys.path:
 METRIC = "W4A8 linear throughput: prefill int8 TOPS (% MFMA peak); decode GB/s (% HBM)"
 INT8_MFMA_PEAK_TOPS = 5000.0       # MI355X dense int8, published
 HBM_PEAK_GBPS = 8000.0             # MI355X HBM3E, published
+# HBM-side bytes per GEMM launch (mean of the four launches of a step) from the two rocprofv3
+# --pmc runs summarised in profiles/gemm_c1_prefill_hbm_traffic_pmc.md (FETCH_SIZE x 2.000,
+# WRITE_SIZE x 1.000, factors from a plain 1 GiB copy).  A counter run cannot happen inside
+# this script; re-measure when the GEMM kernel or its tile order changes.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 171.6e6
 
 
 def parse_args():
@@ -37,9 +42,14 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--decode-layers", type=int, default=28)
-    ap.add_argument("--decode-iters", type=int, default=5)
+    ap.add_argument("--decode-iters", type=int, default=10)
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-graphs", action="store_true",
+                    help="time the decode loop with plain launches instead of one HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (3 launches) so that a counter run "
+                         "has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE with")
     ap.add_argument("--cpu-rows", type=int, default=512,
                     help="rows of the prefill workload the CPU oracle is timed on")
     return ap.parse_args()
@@ -65,6 +75,14 @@ def main():
     from paper_2502_00425_amd import workloads as wl
 
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------ prefill set-up
     w = wl.workload(1)
@@ -160,7 +178,9 @@ def main():
             "bound": "mfma", "kernel": "w4a8_gemm_kernel",
             "achieved": round(gemm_tops / 1e3, 4), "peak": INT8_MFMA_PEAK_TOPS / 1e3,
             "unit": "POP/s (int8; = 1000 TOPS)", "frac": round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
-            "traffic": None,
+            "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH,
+            "algorithmic_bytes_per_launch": sum(l["K"] * l["N"] / 2 + T * l["K"] + 2 * T * l["N"] + 2 * l["N"]
+                                                for l in lin.values()) / n_launch,
             "avg_launch_us": round(gemm_ms * 1e3 / n_launch, 2),
             "ops_per_launch_avg": gemm_ops / n_launch,
             "per_projection": breakdown,
@@ -186,7 +206,8 @@ def bench_decode(args, torch, mq, wl):
     """GEMV over `decode_layers` distinct layers of 7B weights (uniform random
     int4 nibbles written directly in the streamed layout; the contents do not
     change the traffic) for T in {1, 4, 16}, text rows only."""
-    out = {"unit": "GB/s", "peak": HBM_PEAK_GBPS, "layers": args.decode_layers, "per_T": {}}
+    out = {"unit": "GB/s", "peak": HBM_PEAK_GBPS, "layers": args.decode_layers,
+           "launch": "plain" if args.no_graphs else "hipGraph", "per_T": {}}
     gen = torch.Generator(device="cuda")
     gen.manual_seed(3000)
     streams = [torch.cuda.Stream() for _ in range(4)]
@@ -220,14 +241,19 @@ def bench_decode(args, torch, mq, wl):
                     mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
 
         def gemv_streams_pass():
-            # the seven GEMVs of a layer are independent launches here (each has its own
-            # input and output), so they may overlap: round-robin over four streams
+            # The seven GEMVs of a layer are independent launches here (each has its own
+            # input and output buffer), so they may overlap: fork to four streams per layer.
+            main = torch.cuda.current_stream()
             i = 0
             for layer in layers:
+                for s_ in streams:
+                    s_.wait_stream(main)
                 for proj, (K, N, wp, ws) in layer.items():
                     with torch.cuda.stream(streams[i & 3]):
                         mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys_multi[i % len(ys_multi)][N])
                     i += 1
+                for s_ in streams:
+                    main.wait_stream(s_)
 
         bytes_layer = sum(K * N / 2 + 2 * N + T * K + 2 * T * N for (K, N) in wd.projections.values())
         res = {}
@@ -235,9 +261,20 @@ def bench_decode(args, torch, mq, wl):
                          ("gemv_only_4streams", gemv_streams_pass)):
             fn()
             torch.cuda.synchronize()
+            if args.no_graphs:
+                run = fn
+            else:
+                # one HIP graph holds the whole 28-layer pass: the Python launch path
+                # (several microseconds per call) is otherwise the bound
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    fn()
+                run = graph.replay
+                run()
+                torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(args.decode_iters):
-                fn()
+                run()
             torch.cuda.synchronize()
             ms_layer = (time.perf_counter() - t0) * 1e3 / args.decode_iters / len(layers)
             gbps = bytes_layer / (ms_layer * 1e-3) / 1e9
