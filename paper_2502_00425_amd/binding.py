@@ -186,6 +186,10 @@ def w4a8_gemm(xq, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float, s_txt:
     T, K = xq.shape
     if out is None:
         out = torch.empty((T, N), dtype=torch.float16, device=xq.device)
+    if workspace is None:
+        need = w4a8_workspace_bytes(T, N, K)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=xq.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.mquant_w4a8_gemm(_dp(xq), _dp(w_prepacked), _dp(w_scale), _dp(out), out.stride(0),
                                 _dp(acc_out), T, N, K, n_vis, s_vis, s_txt, _dp(workspace),

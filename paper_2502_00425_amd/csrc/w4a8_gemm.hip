@@ -174,7 +174,8 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
     const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
     __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
     int32_t K, int32_t n_vis, float s_vis, float s_txt, int32_t tiles_m, int32_t tiles_n,
-    int32_t n_tiles32)
+    int32_t n_tiles32, int32_t splits, int32_t kb_per_split, int32_t *__restrict__ partial,
+    int32_t wide_store)
 {
     constexpr int NW = WM * WN;
     constexpr int MT = BM / WM / 32;          // 32x32 tiles per wave along M
@@ -188,8 +189,11 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
+    // With split-K the K range is one more factor of the tile grid (next to tn).
     int32_t tm, tn;
-    tile_of_group<BAND>(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    tile_of_group<BAND>(blockIdx.x, tiles_m, tiles_n * splits, tm, tn);
+    const int32_t split = tn % splits;
+    tn /= splits;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -201,7 +205,9 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
 
     const int32_t row0 = tm * BM;
     const int32_t k_tiles = K / kPackK;
-    const int32_t k_blocks = K / 128;         // K % 128 == 0 is guaranteed by the host
+    const int32_t kb0 = split * kb_per_split;           // first 128-wide k-block of this group
+    int32_t k_blocks = K / 128 - kb0;                   // K % 128 == 0 is guaranteed by the host
+    k_blocks = k_blocks < kb_per_split ? k_blocks : kb_per_split;
     const int32_t ntile0 = tn * (BN / 32);
 
     v16i acc[MT][NT];
@@ -226,14 +232,14 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
             int32_t row = row0 + r;
             row = row < T ? row : T - 1;
             src[j] = reinterpret_cast<const uint8_t *>(xq) + static_cast<int64_t>(row) * K +
-                     logical * 16;
+                     static_cast<int64_t>(kb0) * 128 + logical * 16;
             src_step[j] = 128;
         } else {
             const int b = q - A_CH, nt = b >> 1, ks = b & 1;
             int32_t ntile = ntile0 + nt;
             ntile = ntile < n_tiles32 ? ntile : n_tiles32 - 1;
             src[j] = reinterpret_cast<const uint8_t *>(wp) +
-                     ((static_cast<int64_t>(ntile) * k_tiles + ks) * 64 + lane) * 16;
+                     ((static_cast<int64_t>(ntile) * k_tiles + kb0 * 2 + ks) * 64 + lane) * 16;
             src_step[j] = 2 * kPackTileBytes;
         }
     }
@@ -293,23 +299,130 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
         nbuf = nbuf + 1 == STAGES ? 0 : nbuf + 1;
     }
 
-    // ---- epilogue: scale select by row span, per-channel scale, fp16 store
+    const int32_t wave_row0 = row0 + wm * (BM / WM);
+    const int32_t wave_n0 = (ntile0 + wn * NT) * 32;
+
+    // ---- split-K: hand the raw partial sums (still x16) to the reduce kernel
+    if (partial != nullptr) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int32_t n = (ntile0 + wn * NT + nt) * 32 + l32;
-        if (n >= N) continue;
-        const float ws = __half2float(w_scale[n]);
+        for (int nt = 0; nt < NT; ++nt) {
+            const int32_t n = wave_n0 + nt * 32 + l32;
+            if (n >= N) continue;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int32_t row = row0 + wm * (BM / WM) + mt * 32 + acc_row(r, g);
-                if (row < T) {
-                    const float s_row = row < n_vis ? s_vis : s_txt;
-                    store_out(acc[mt][nt][r], row, n, s_row, ws, y, ldy, acc_out, N);
+                for (int r = 0; r < 16; ++r) {
+                    const int32_t row = wave_row0 + mt * 32 + acc_row(r, g);
+                    if (row < T)
+                        partial[(static_cast<int64_t>(split) * T + row) * N + n] = acc[mt][nt][r];
+                }
+        }
+        return;
+    }
+
+    // ---- epilogue: scale select by row span, per-channel scale, fp16
+    if (!wide_store || acc_out != nullptr) {
+        // plain path: every lane stores its own 2-byte results
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int32_t n = wave_n0 + nt * 32 + l32;
+            if (n >= N) continue;
+            const float ws = __half2float(w_scale[n]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int32_t row = wave_row0 + mt * 32 + acc_row(r, g);
+                    if (row < T) {
+                        const float s_row = row < n_vis ? s_vis : s_txt;
+                        store_out(acc[mt][nt][r], row, n, s_row, ws, y, ldy, acc_out, N);
+                    }
                 }
             }
         }
+        return;
+    }
+
+    // Wide path: the MFMA result has a lane per column, so a direct store writes
+    // 2 bytes per lane.  Each wave instead turns 32 rows x (NT*32) columns through
+    // its own LDS patch and stores 16 bytes per lane, whole rows of the patch
+    // (NT*64 contiguous bytes) at a time.
+    constexpr int ROWB = NT * 64 + 16;                 // padded row pitch of the patch, bytes
+    constexpr int LPR = NT * 64 / 16;                  // lanes per patch row on the way out
+    constexpr int RPI = 64 / LPR;                      // patch rows per store instruction
+    static_assert(NW * 32 * ROWB <= STAGES * STAGE, "epilogue patch must fit the stage buffers");
+    __syncthreads();                                   // every wave is done with the stage buffers
+    uint8_t *patch = smem + wave * (32 * ROWB);
+    float ws[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int32_t n = wave_n0 + nt * 32 + l32;
+        ws[nt] = __half2float(w_scale[n < N ? n : N - 1]);
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rl = acc_row(r, g);
+            const int32_t row = wave_row0 + mt * 32 + rl;
+            const float s_row = row < n_vis ? s_vis : s_txt;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int32_t a = acc[mt][nt][r] >> 4;             // exact: the sum holds 16 * acc
+                const float v = (static_cast<float>(a) * s_row) * ws[nt];
+                *reinterpret_cast<__half *>(patch + rl * ROWB + (nt * 32 + l32) * 2) =
+                    __float2half_rn(v);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 32 / RPI; ++q) {
+            const int rl = q * RPI + lane / LPR;
+            const int c = lane % LPR;
+            const uint4 v = *reinterpret_cast<const uint4 *>(patch + rl * ROWB + c * 16);
+            const int32_t row = wave_row0 + mt * 32 + rl;
+            const int32_t n = wave_n0 + c * 8;
+            if (row < T && n < N)                                  // N % 8 == 0 on this path
+                *reinterpret_cast<uint4 *>(y + static_cast<int64_t>(row) * ldy + n) = v;
+        }
+    }
+}
+
+// Sums the split-K partials (int32, x16) and applies the dequant epilogue.
+// Four consecutive channels per thread; N % 4 == 0.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(
+    const int32_t *__restrict__ partial, int32_t splits, int32_t T, int32_t N,
+    const __half *__restrict__ w_scale, __half *__restrict__ y, int64_t ldy,
+    int32_t *__restrict__ acc_out, int32_t n_vis, float s_vis, float s_txt)
+{
+    const int64_t quads = static_cast<int64_t>(T) * (N / 4);
+    const int64_t plane = static_cast<int64_t>(T) * N;
+    for (int64_t q = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; q < quads;
+         q += static_cast<int64_t>(gridDim.x) * 256) {
+        const int32_t row = static_cast<int32_t>(q / (N / 4));
+        const int32_t n = static_cast<int32_t>(q - static_cast<int64_t>(row) * (N / 4)) * 4;
+        const int64_t off = static_cast<int64_t>(row) * N + n;
+        int4 sum = *reinterpret_cast<const int4 *>(partial + off);
+        for (int32_t s = 1; s < splits; ++s) {
+            const int4 p = *reinterpret_cast<const int4 *>(partial + s * plane + off);
+            sum.x += p.x;
+            sum.y += p.y;
+            sum.z += p.z;
+            sum.w += p.w;
+        }
+        const float s_row = row < n_vis ? s_vis : s_txt;
+        const int32_t a[4] = {sum.x >> 4, sum.y >> 4, sum.z >> 4, sum.w >> 4};
+        __half h[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            h[j] = __float2half_rn((static_cast<float>(a[j]) * s_row) * __half2float(w_scale[n + j]));
+        __half *dst = y + static_cast<int64_t>(row) * ldy + n;
+        if ((reinterpret_cast<uintptr_t>(dst) & 7) == 0) {
+            *reinterpret_cast<uint2 *>(dst) = *reinterpret_cast<const uint2 *>(h);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dst[j] = h[j];
+        }
+        if (acc_out) *reinterpret_cast<int4 *>(acc_out + off) = make_int4(a[0], a[1], a[2], a[3]);
     }
 }
 
@@ -434,15 +547,35 @@ int check_gemm_args(const void *xq, const void *wp, const void *w_scale, const v
     return MQUANT_OK;
 }
 
+constexpr int kNumCU = 256;
+
+// Split-K plan for the 256x256 tile: when the tile grid fills less than half of
+// the CUs and K is long, S work-groups share a tile's K range, write int32
+// partials to the workspace and a small second kernel reduces and dequantises.
+// (A single-kernel reduction needs device-scope fences, which write back the
+// whole L2 and were measured far slower.)
+int plan_splits(int32_t T, int32_t N, int32_t K)
+{
+    const int64_t tiles = ceil_div(T, 256) * ceil_div(N, 256);
+    int64_t s = kNumCU / tiles;
+    if (s < 2 || N % 4 != 0) return 1;
+    if (s > 4) s = 4;
+    while (s > 1 && K / s < 4096) --s;
+    return static_cast<int>(s);
+}
+
 template <int BM, int BN, int WM, int WN, int STAGES, int BAND>
 int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y, int64_t ldy,
                 int32_t *acc_out, int32_t T, int32_t N, int32_t K, int32_t n_vis, float s_vis,
-                float s_txt, hipStream_t stream)
+                float s_txt, int32_t splits, int32_t *partial, hipStream_t stream)
 {
     const int32_t tiles_m = static_cast<int32_t>(ceil_div(T, BM));
     const int32_t tiles_n = static_cast<int32_t>(ceil_div(N, BN));
     const int32_t n_tiles32 = static_cast<int32_t>(ceil_div(N, kPackN));
+    const int32_t kb_per_split = static_cast<int32_t>(ceil_div(K / 128, splits));
     const size_t lds = static_cast<size_t>(STAGES) * (BM * 128 + BN * 64);
+    const int32_t wide_store =
+        (N % 8 == 0 && ldy % 8 == 0 && aligned_to(y, 16) && acc_out == nullptr) ? 1 : 0;
     auto kern = w4a8_gemm_kernel<BM, BN, WM, WN, STAGES, BAND>;
     static bool attr_set = false;       // raising the dynamic LDS limit is idempotent
     if (!attr_set) {
@@ -452,10 +585,19 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
             return MQUANT_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * 64), lds, stream, xq,
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(WM * WN * 64), lds, stream, xq,
                        reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
                        static_cast<__half *>(y), ldy, acc_out, T, N, K, n_vis, s_vis, s_txt,
-                       tiles_m, tiles_n, n_tiles32);
+                       tiles_m, tiles_n, n_tiles32, splits, kb_per_split,
+                       splits > 1 ? partial : nullptr, wide_store);
+    int st = launch_status();
+    if (st != MQUANT_OK || splits == 1) return st;
+    const int64_t quads = static_cast<int64_t>(T) * (N / 4);
+    int64_t blocks = ceil_div(quads, 256);
+    if (blocks > 8 * kNumCU) blocks = 8 * kNumCU;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
+                       stream, partial, splits, T, N, static_cast<const __half *>(w_scale),
+                       static_cast<__half *>(y), ldy, acc_out, n_vis, s_vis, s_txt);
     return launch_status();
 }
 
@@ -464,8 +606,6 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
 // hides one group's prologue and epilogue under the other's main loop and
 // halves the tile-count granularity.  Cost model: rounds over the 256 CUs times
 // tile area, the smaller tile derated by its measured relative rate.
-constexpr int kNumCU = 256;
-
 int pick_gemm_tile(int32_t T, int32_t N)
 {
     const double a = static_cast<double>(ceil_div(ceil_div(T, 256) * ceil_div(N, 256), kNumCU)) *
@@ -507,7 +647,9 @@ extern "C" int64_t mquant_w4a8_workspace_bytes(int32_t T, int32_t N, int32_t K)
 {
     if (T < 0 || N < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
     if (K % kPackK != 0 || K > kMaxK) return MQUANT_ERR_UNSUPPORTED;
-    return 0;
+    if (T <= kGemvMaxT || K % 128 != 0) return 0;
+    const int splits = plan_splits(T, N, K);
+    return splits > 1 ? static_cast<int64_t>(splits) * T * N * 4 : 0;
 }
 
 extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y,
@@ -515,8 +657,6 @@ extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void 
                                 int32_t n_vis, float s_vis, float s_txt, void *workspace,
                                 int64_t workspace_bytes, mquant_stream_t stream_)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     const int st = check_gemm_args(xq, wp, w_scale, y, ldy, T, N, K, n_vis, s_vis, s_txt);
     if (st != MQUANT_OK) return st;
     if (T == 0 || N == 0) return MQUANT_OK;
@@ -549,11 +689,20 @@ extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void 
         }
         return MQUANT_OK;
     }
+    const int splits = plan_splits(T, N, K);
+    if (splits > 1) {
+        const int64_t need = static_cast<int64_t>(splits) * T * N * 4;
+        if (!workspace || workspace_bytes < need) return MQUANT_ERR_WORKSPACE;
+        if (!aligned_to(workspace, 256)) return MQUANT_ERR_ALIGNMENT;
+        return launch_gemm<256, 256, 2, 4, 3, 4>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
+                                                 s_vis, s_txt, splits,
+                                                 static_cast<int32_t *>(workspace), stream);
+    }
     if (pick_gemm_tile(T, N) == 0)
         return launch_gemm<256, 256, 2, 4, 3, 4>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
-                                                 s_vis, s_txt, stream);
+                                                 s_vis, s_txt, 1, nullptr, stream);
     return launch_gemm<128, 256, 2, 4, 2, 8>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
-                                             s_vis, s_txt, stream);
+                                             s_vis, s_txt, 1, nullptr, stream);
 }
 
 extern "C" int64_t mquant_w4a8_linear_prefill_workspace_bytes(int32_t T, int32_t N, int32_t K)
