@@ -23,6 +23,7 @@
 // K <= 65536.
 #include <hip/hip_fp16.h>
 #include <math.h>
+#include <stdlib.h>
 
 #include "mquant_internal.h"
 
@@ -151,11 +152,10 @@ __device__ __forceinline__ int lds_a_offset(int row, int chunk)
 
 // Work-group id -> (tm, tn).  Work-groups are dealt round-robin to the 8 XCDs,
 // each with its own L2: XCD x gets a contiguous run of the tile order, and the
-// order walks bands of BAND tile-rows, so the ~32 tiles an XCD runs at a time
+// order walks bands of `band` tile-rows, so the ~32 tiles an XCD runs at a time
 // form a compact block that shares few A row-panels and few B column-panels.
-template <int BAND>
 __device__ __forceinline__ void tile_of_group(int32_t id, int32_t tiles_m, int32_t tiles_n,
-                                              int32_t &tm, int32_t &tn)
+                                              int32_t BAND, int32_t &tm, int32_t &tn)
 {
     const int32_t total = tiles_m * tiles_n;
     const int32_t per = total / 8, rem = total % 8;
@@ -169,13 +169,13 @@ __device__ __forceinline__ void tile_of_group(int32_t id, int32_t tiles_m, int32
     tn = in_band / rows;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int BAND>
+template <int BM, int BN, int WM, int WN, int STAGES>
 __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
     const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
     __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
     int32_t K, int32_t n_vis, float s_vis, float s_txt, int32_t tiles_m, int32_t tiles_n,
     int32_t n_tiles32, int32_t splits, int32_t kb_per_split, int32_t *__restrict__ partial,
-    int32_t wide_store)
+    int32_t wide_store, int32_t band)
 {
     constexpr int NW = WM * WN;
     constexpr int MT = BM / WM / 32;          // 32x32 tiles per wave along M
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
 
     // With split-K the K range is one more factor of the tile grid (next to tn).
     int32_t tm, tn;
-    tile_of_group<BAND>(blockIdx.x, tiles_m, tiles_n * splits, tm, tn);
+    tile_of_group(blockIdx.x, tiles_m, tiles_n * splits, band, tm, tn);
     const int32_t split = tn % splits;
     tn /= splits;
 
@@ -564,7 +564,7 @@ int plan_splits(int32_t T, int32_t N, int32_t K)
     return static_cast<int>(s);
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int BAND>
+template <int BM, int BN, int WM, int WN, int STAGES>
 int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y, int64_t ldy,
                 int32_t *acc_out, int32_t T, int32_t N, int32_t K, int32_t n_vis, float s_vis,
                 float s_txt, int32_t splits, int32_t *partial, hipStream_t stream)
@@ -576,7 +576,11 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
     const size_t lds = static_cast<size_t>(STAGES) * (BM * 128 + BN * 64);
     const int32_t wide_store =
         (N % 8 == 0 && ldy % 8 == 0 && aligned_to(y, 16) && acc_out == nullptr) ? 1 : 0;
-    auto kern = w4a8_gemm_kernel<BM, BN, WM, WN, STAGES, BAND>;
+    auto kern = w4a8_gemm_kernel<BM, BN, WM, WN, STAGES>;
+    // Band height of the tile order: all tile-rows when there are few (every B panel is then
+    // read by one XCD only), else equal bands of about six rows.
+    const int32_t band = tiles_m <= 8 ? tiles_m
+                                      : static_cast<int32_t>(ceil_div(tiles_m, ceil_div(tiles_m, 6)));
     static bool attr_set = false;       // raising the dynamic LDS limit is idempotent
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -589,7 +593,7 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
                        reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
                        static_cast<__half *>(y), ldy, acc_out, T, N, K, n_vis, s_vis, s_txt,
                        tiles_m, tiles_n, n_tiles32, splits, kb_per_split,
-                       splits > 1 ? partial : nullptr, wide_store);
+                       splits > 1 ? partial : nullptr, wide_store, band);
     int st = launch_status();
     if (st != MQUANT_OK || splits == 1) return st;
     const int64_t quads = static_cast<int64_t>(T) * (N / 4);
@@ -689,19 +693,22 @@ extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void 
         }
         return MQUANT_OK;
     }
-    const int splits = plan_splits(T, N, K);
+    int splits = plan_splits(T, N, K);
+    int force_tile = -1;
+    if (const char *e = getenv("MQUANT_TUNE_TILE")) { if (*e) force_tile = atoi(e); }
+    if (const char *e = getenv("MQUANT_TUNE_NOSPLIT")) { if (atoi(e)) splits = 1; }
     if (splits > 1) {
         const int64_t need = static_cast<int64_t>(splits) * T * N * 4;
         if (!workspace || workspace_bytes < need) return MQUANT_ERR_WORKSPACE;
         if (!aligned_to(workspace, 256)) return MQUANT_ERR_ALIGNMENT;
-        return launch_gemm<256, 256, 2, 4, 3, 4>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
+        return launch_gemm<256, 256, 2, 4, 3>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
                                                  s_vis, s_txt, splits,
                                                  static_cast<int32_t *>(workspace), stream);
     }
-    if (pick_gemm_tile(T, N) == 0)
-        return launch_gemm<256, 256, 2, 4, 3, 4>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
+    if ((force_tile < 0 ? pick_gemm_tile(T, N) : force_tile) == 0)
+        return launch_gemm<256, 256, 2, 4, 3>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
                                                  s_vis, s_txt, 1, nullptr, stream);
-    return launch_gemm<128, 256, 2, 4, 2, 8>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
+    return launch_gemm<128, 256, 2, 4, 2>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
                                              s_vis, s_txt, 1, nullptr, stream);
 }
 
