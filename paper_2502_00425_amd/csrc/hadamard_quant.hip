@@ -67,14 +67,48 @@ template <int B, int M>
 __device__ __forceinline__ void lane_stage(float (&v)[8], int lane)
 {
     if constexpr (8 * M < B) {
-        // The lane holding the lower index keeps a + b, the other one a - b with a
-        // the lower-index value: other + (upper ? -mine : mine), one add per value.
-        const int sign = (lane & M) ? static_cast<int>(0x80000000u) : 0;
+        if constexpr (M < 16) {
+            // The lane holding the lower index keeps a + b, the other one a - b with
+            // a the lower-index value: other + (upper ? -mine : mine), one add each.
+            const int sign = (lane & M) ? static_cast<int>(0x80000000u) : 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float other = lane_xor<M>(v[j], lane);
-            const float mine = __int_as_float(__float_as_int(v[j]) ^ sign);
-            v[j] = other + mine;
+            for (int j = 0; j < 8; ++j) {
+                const float other = lane_xor<M>(v[j], lane);
+                const float mine = __int_as_float(__float_as_int(v[j]) ^ sign);
+                v[j] = other + mine;
+            }
+        } else {
+            // Partner lanes sit in different rows (M = 16) or wave halves (M = 32).
+            // The row / half swap instructions exchange the odd rows (upper half)
+            // of one register with the even rows (lower half) of another: applied to
+            // (v[j], v[j+4]) it leaves every lane with a complete pair (a, b) -- the
+            // lower-index lanes for register j, the upper-index lanes for j+4 --
+            // so each lane does one add and one subtract, and the same swap puts the
+            // results back where they belong.  No select, no LDS.
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int lo = __float_as_int(v[j]), hi = __float_as_int(v[j + 4]);
+                float a, b;
+                if constexpr (M == 16) {
+                    const auto sw = __builtin_amdgcn_permlane16_swap(lo, hi, false, false);
+                    a = __int_as_float(sw[0]);
+                    b = __int_as_float(sw[1]);
+                } else {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
+                    a = __int_as_float(sw[0]);
+                    b = __int_as_float(sw[1]);
+                }
+                const int p = __float_as_int(a + b), q = __float_as_int(a - b);
+                if constexpr (M == 16) {
+                    const auto sw = __builtin_amdgcn_permlane16_swap(p, q, false, false);
+                    v[j] = __int_as_float(sw[0]);
+                    v[j + 4] = __int_as_float(sw[1]);
+                } else {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(p, q, false, false);
+                    v[j] = __int_as_float(sw[0]);
+                    v[j + 4] = __int_as_float(sw[1]);
+                }
+            }
         }
     }
 }
@@ -169,13 +203,22 @@ __global__ __launch_bounds__(256) void hadamard_quant_kernel(
 #pragma unroll
             for (int c = 0; c < C; ++c) {
                 if (valid[c]) {
-                    uint32_t packed[2] = {0u, 0u};
+                    // clamp(rint(t)) == rint(clamp(t)) for integer bounds; adding 1.5 * 2^23
+                    // rounds to an integer (ties to even) and leaves it in the low mantissa
+                    // bits, whose low byte is the two's-complement int8 code.
+                    uint32_t bits[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        float r = __builtin_rintf(v[c][j] * cmul);      // ties to even
-                        r = fminf(fmaxf(r, -128.0f), 127.0f);
-                        const int32_t q = static_cast<int32_t>(r);
-                        packed[j >> 2] |= (static_cast<uint32_t>(q) & 0xFFu) << (8 * (j & 3));
+                        const float t = __builtin_amdgcn_fmed3f(v[c][j] * cmul, -128.0f, 127.0f);
+                        bits[j] = __float_as_uint(t + 12582912.0f);
+                    }
+                    uint32_t packed[2];
+#pragma unroll
+                    for (int w = 0; w < 2; ++w) {
+                        // byte 0 of four words -> one dword
+                        const uint32_t p01 = __builtin_amdgcn_perm(bits[4 * w + 1], bits[4 * w], 0x0c0c0400u);
+                        const uint32_t p23 = __builtin_amdgcn_perm(bits[4 * w + 3], bits[4 * w + 2], 0x04000c0cu);
+                        packed[w] = p01 | p23;
                     }
                     const int64_t k0 = static_cast<int64_t>(sidx) * SEG + c * 512 + lane * 8;
                     *reinterpret_cast<uint2 *>(xq + static_cast<int64_t>(i) * K + k0) =
