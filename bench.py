@@ -11,7 +11,8 @@ Inputs are resident in HBM before the timed region.
 
 Prints ONE JSON line.  `value` is prefill int8 TOPS = 2*T*sum(K*N) / step time.
 `roofline` covers the dominant kernel (the MFMA GEMM), its duration measured
-with HIP events inside the timed steps.  `decode` reports the weight-streaming
+with HIP events in a second pass over the same steps (the event pairs themselves
+cost idle time, so the pass that gives `value` runs without them).  `decode` reports the weight-streaming
 GEMV (T in {1,4,16}) over 28 distinct layers of weights (3.1 GB, more than the
 256 MB last-level cache) in GB/s.  `cpu_baseline` times the CPU oracle on a
 bounded row sample of the same workload.
@@ -113,57 +114,85 @@ def main():
     x_u = torch.empty_like(x_embed)
     gemm_ops = sum(2.0 * T * l["K"] * l["N"] for l in lin.values())
 
-    ev_pairs = []      # (proj, start, end) around every GEMM launch of the timed steps
+    ev_pairs = []      # (kind, proj, start, end) around kernel launches of the instrumented steps
+
+    def bracket(record, kind, proj, fn):
+        if not record:
+            fn()
+            return
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        ev_pairs.append((kind, proj, e0, e1))
 
     def step(record: bool):
         mq.aifs_remap_mask(mask, permd, out=mask_u)
         mq.aifs_permute(x_embed, permd, out=x_u)
         for proj, l in lin.items():
-            mq.hadamard_quant_act(l["x"], V, l["s_vis"], l["s_txt"], B, perm_dev=permd, out=l["xq"])
-            if record:
-                e0 = torch.cuda.Event(enable_timing=True)
-                e1 = torch.cuda.Event(enable_timing=True)
-                e0.record()
-            mq.w4a8_gemm(l["xq"], l["wp"], l["w_scale"], l["N"], V, l["s_vis"], l["s_txt"],
-                         out=l["y"], workspace=l["ws"])
-            if record:
-                e1.record()
-                ev_pairs.append((proj, e0, e1))
+            bracket(record, "quant", proj, lambda: mq.hadamard_quant_act(
+                l["x"], V, l["s_vis"], l["s_txt"], B, perm_dev=permd, out=l["xq"]))
+            bracket(record, "gemm", proj, lambda: mq.w4a8_gemm(
+                l["xq"], l["wp"], l["w_scale"], l["N"], V, l["s_vis"], l["s_txt"],
+                out=l["y"], workspace=l["ws"]))
 
+    # Timed region 1: exactly `steps` steps, no instrumentation -> value.
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(True)
+        step(False)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tops = gemm_ops / (ms_per_step * 1e-3) / 1e12
 
+    # Timed region 2: the same `steps` steps again with a HIP event pair around every
+    # rotate+quant and GEMM launch (an event pair costs about 5 us of idle time around the
+    # kernel it brackets, which is why region 1 runs without them).
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+
     per_proj_ms = {p: 0.0 for p in lin}
-    for proj, e0, e1 in ev_pairs:
-        per_proj_ms[proj] += e0.elapsed_time(e1)
+    fe_ms = 0.0
+    for kind, proj, e0, e1 in ev_pairs:
+        if kind == "gemm":
+            per_proj_ms[proj] += e0.elapsed_time(e1)
+        else:
+            fe_ms += e0.elapsed_time(e1)
     for p in per_proj_ms:
         per_proj_ms[p] /= args.steps
+    fe_ms /= args.steps
     gemm_ms = sum(per_proj_ms.values())
     n_launch = len(lin)
     gemm_tops = gemm_ops / (gemm_ms * 1e-3) / 1e12
     breakdown = {p: {"gemm_us": round(per_proj_ms[p] * 1e3, 2),
                      "tops": round(2.0 * T * lin[p]["K"] * lin[p]["N"] / (per_proj_ms[p] * 1e-3) / 1e12, 1)}
                  for p in lin}
-
-    # front-end (rotate + quant) timed on its own, for the record
     fe_bytes = sum(3.0 * T * l["K"] for l in lin.values())
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = 20
-    e0.record()
-    for _ in range(reps):
-        for proj, l in lin.items():
-            mq.hadamard_quant_act(l["x"], V, l["s_vis"], l["s_txt"], B, perm_dev=permd, out=l["xq"])
-    e1.record()
-    torch.cuda.synchronize()
-    fe_ms = e0.elapsed_time(e1) / reps
+    # Front end on its own: the four rotate+quant launches back to back inside one HIP graph
+    # (event pairs around 6-20 us kernels mostly measure the events).
+    def fe_pass():
+        for _ in range(10):
+            for proj, l in lin.items():
+                mq.hadamard_quant_act(l["x"], V, l["s_vis"], l["s_txt"], B, perm_dev=permd, out=l["xq"])
+    fe_event_ms = fe_ms
+    if not args.no_graphs:
+        fe_pass()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fe_pass()
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            g.replay()
+        torch.cuda.synchronize()
+        fe_ms = (time.perf_counter() - t0) * 1e3 / 50
 
     result = {
         "metric": METRIC, "value": round(tops, 2), "unit": "TOPS",
