@@ -250,10 +250,24 @@ def bench_decode(args, torch, mq, wl):
             ws = (torch.rand(N, device="cuda", generator=gen) * 0.015 + 0.005).half()
             layer[proj] = (K, N, wp, ws)
         layers.append(layer)
+    # The same weights grouped as a decoder layer launches them when q/k/v and gate/up are
+    # fused (as in the prefill configuration): qkv N=4608, o, gate_up N=37888, down.  In the
+    # streamed layout concatenating along N is concatenating the buffers.
+    fused_layers = []
+    for layer in layers:
+        f = {}
+        f["qkv"] = (3584, 4608, torch.cat([layer[p][2] for p in ("q", "k", "v")]),
+                    torch.cat([layer[p][3] for p in ("q", "k", "v")]))
+        f["o"] = layer["o"]
+        f["gate_up"] = (3584, 37888, torch.cat([layer[p][2] for p in ("gate", "up")]),
+                        torch.cat([layer[p][3] for p in ("gate", "up")]))
+        f["down"] = layer["down"]
+        fused_layers.append(f)
     for T in (1, 4, 16):
         xs = {K: torch.randn((T, K), device="cuda", generator=gen).half() for K in (3584, 18944)}
         xq = {K: torch.empty((T, K), dtype=torch.int8, device="cuda") for K in xs}
-        ys = {N: torch.empty((T, N), dtype=torch.float16, device="cuda") for N in (3584, 512, 18944)}
+        ys = {N: torch.empty((T, N), dtype=torch.float16, device="cuda")
+              for N in (3584, 512, 18944, 4608, 37888)}
         ys_multi = [{N: torch.empty((T, N), dtype=torch.float16, device="cuda") for N in (3584, 512, 18944)}
                     for _ in range(8)]
         s_txt = 0.035
@@ -269,24 +283,32 @@ def bench_decode(args, torch, mq, wl):
                 for proj, (K, N, wp, ws) in layer.items():
                     mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
 
+        def gemv_fused_pass():
+            for layer in fused_layers:
+                for proj, (K, N, wp, ws) in layer.items():
+                    mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
+
         def gemv_streams_pass():
-            # The seven GEMVs of a layer are independent launches here (each has its own
-            # input and output buffer), so they may overlap: fork to four streams per layer.
+            # Kernel throughput when launches overlap: the GEMVs here have no data dependence
+            # on each other (own input and output buffers), so four independent stream chains
+            # share the pass and join once at its end.  A real decode step is a dependent
+            # chain; this leg only shows what the kernel streams when the launch gaps are hidden.
             main = torch.cuda.current_stream()
+            for s_ in streams:
+                s_.wait_stream(main)
             i = 0
             for layer in layers:
-                for s_ in streams:
-                    s_.wait_stream(main)
                 for proj, (K, N, wp, ws) in layer.items():
                     with torch.cuda.stream(streams[i & 3]):
                         mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys_multi[i % len(ys_multi)][N])
                     i += 1
-                for s_ in streams:
-                    main.wait_stream(s_)
+            for s_ in streams:
+                main.wait_stream(s_)
 
         bytes_layer = sum(K * N / 2 + 2 * N + T * K + 2 * T * N for (K, N) in wd.projections.values())
         res = {}
         for name, fn in (("quant+gemv", one_pass), ("gemv_only", gemv_only_pass),
+                         ("gemv_only_fused_qkv_gateup", gemv_fused_pass),
                          ("gemv_only_4streams", gemv_streams_pass)):
             fn()
             torch.cuda.synchronize()

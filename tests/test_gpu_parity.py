@@ -240,6 +240,48 @@ def test_gemm_small_shapes_full(mq, T, N, K, V):
     assert (y2.view(np.uint16) == yb[:, :N].view(np.uint16)).all()
 
 
+@pytest.mark.parametrize("T,N,K,V,ldy_pad", [
+    (300, 520, 8192, 77, 0),     # split-K (few tiles, long K), ragged T and N, wide stores
+    (300, 516, 8192, 300, 4),    # split-K with N % 8 != 0: plain stores in the reduce kernel
+    (70, 250, 16384, 0, 0),      # N % 4 != 0: split-K is not taken
+    (513, 264, 4096, 512, 0),    # one row past two 256-row tiles, K too short to split
+])
+def test_gemm_split_k_and_store_paths(mq, T, N, K, V, ldy_pad):
+    say(f"gemm split/store paths T={T} N={N} K={K}")
+    rng = np.random.default_rng(T + N + K)
+    xq = rng.integers(-128, 128, size=(T, K), dtype=np.int8)
+    packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+    s_vis, s_txt = 0.11, 0.004
+    acc_want = orc.gemm_i8_i4_i32(xq, orc.unpack_w4(packed))
+    ref, _ = orc.dequant(acc_want, V, s_vis, s_txt, w_scale)
+    wp = mq.w4_prepack(dev(packed))
+    ws_bytes = mq.w4a8_workspace_bytes(T, N, K)
+    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device="cuda")
+    ldy = N + ldy_pad
+    for want_acc in (False, True):
+        ybuf = torch.full((T, ldy), 7.0, dtype=torch.float16, device="cuda")
+        acc = torch.full((T, N), -3, dtype=torch.int32, device="cuda") if want_acc else None
+        mq.w4a8_gemm(dev(xq), wp, dev(w_scale), N, V, s_vis, s_txt, out=ybuf[:, :N], acc_out=acc,
+                     workspace=ws if ws_bytes else None)
+        yb = ybuf.cpu().numpy()
+        check_y(yb[:, :N], ref, f"split/store want_acc={want_acc}")
+        assert (yb[:, N:] == 7.0).all()
+        if want_acc:
+            assert (acc.cpu().numpy() == acc_want).all()
+
+
+def test_gemm_workspace_is_required_when_split(mq):
+    T, N, K = 300, 520, 8192
+    assert mq.w4a8_workspace_bytes(T, N, K) > 0
+    xq = torch.zeros((T, K), dtype=torch.int8, device="cuda")
+    wp = torch.zeros(mq.w4_prepacked_bytes(N, K), dtype=torch.uint8, device="cuda")
+    y = torch.empty((T, N), dtype=torch.float16, device="cuda")
+    st = mq.lib.mquant_w4a8_gemm(xq.data_ptr(), wp.data_ptr(), torch.ones(N, dtype=torch.float16, device="cuda").data_ptr(),
+                                 y.data_ptr(), N, None, T, N, K, 0, 1.0, 1.0, None, 0, None)
+    assert st == mq.ERR_WORKSPACE
+
+
 def test_gemm_extreme_values_no_overflow(mq):
     say("gemm extremes K=29568")
     K, T, N = 29568, 64, 64
