@@ -32,9 +32,9 @@ INT8_MFMA_PEAK_TOPS = 5000.0       # MI355X dense int8, published
 HBM_PEAK_GBPS = 8000.0             # MI355X HBM3E, published
 # HBM-side bytes per GEMM launch (mean of the four launches of a step) from the two rocprofv3
 # --pmc runs summarised in profiles/gemm_c1_prefill_hbm_traffic_pmc.md (FETCH_SIZE x 2.000,
-# WRITE_SIZE x 1.000, factors from a plain 1 GiB copy).  A counter run cannot happen inside
+# WRITE_SIZE x 1.000, factors from a plain 1 GiB copy; includes the split-K partials of down).  A counter run cannot happen inside
 # this script; re-measure when the GEMM kernel or its tile order changes.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 171.6e6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 183.0e6
 
 
 def parse_args():
