@@ -13,6 +13,11 @@ import os
 from typing import Optional, Sequence, Tuple
 
 import numpy as np
+# torch before libmquant.so: the ROCm wheel of torch carries its own HIP runtime under the
+# same soname.  Loaded second, libmquant binds to that copy and shares torch's streams and
+# memory; loaded first, it would pull in the system runtime as a second one in the process,
+# and a second runtime may find no device to open.
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libmquant.so")

@@ -116,7 +116,7 @@ extern "C" int mquant_aifs_permute(const void *x, int64_t ldx, void *x_u, int64_
     const int32_t chunks = K / 8;
     dim3 grid(static_cast<unsigned>(ceil_div(chunks, 256)),
               static_cast<unsigned>(T < 65535 ? T : 65535));
-    hipLaunchKernelGGL(permute_rows_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
+    MQ_LAUNCH(permute_rows_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint4 *>(x), ldx / 8, static_cast<uint4 *>(x_u), ldxu / 8,
                        perm, T, chunks);
     return launch_status();
@@ -131,7 +131,7 @@ extern "C" int mquant_aifs_remap_mask(const uint8_t *mask, uint8_t *mask_u, cons
     if (!aligned_to(mask_u, 4) || !aligned_to(perm, 16)) return MQUANT_ERR_ALIGNMENT;
     dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(T, 4), 256)),
               static_cast<unsigned>(T < 65535 ? T : 65535));
-    hipLaunchKernelGGL(remap_mask_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
+    MQ_LAUNCH(remap_mask_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
                        mask, mask_u, perm, T);
     return launch_status();
 }

@@ -249,7 +249,7 @@ int launch(const void *x, int64_t ldx, const int32_t *perm, int8_t *xq, int32_t 
     const __half *xh = static_cast<const __half *>(x);
 #define MQ_CASE(BV)                                                                          \
     case BV:                                                                                 \
-        hipLaunchKernelGGL((hadamard_quant_kernel<BV, ABSMAX>), grid, block, 0, stream, xh,  \
+        MQ_LAUNCH((hadamard_quant_kernel<BV, ABSMAX>), grid, block, 0, stream, xh,  \
                            ldx, perm, xq, T, K, n_vis, c_vis, c_txt, segs_per_row, absmax);  \
         break;
     switch (B) {

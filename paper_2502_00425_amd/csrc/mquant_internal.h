@@ -2,6 +2,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <cstdio>
+#include <cstdlib>
 #include <stdint.h>
 
 #include "mquant.h"
@@ -15,9 +17,23 @@ static inline bool aligned_to(const void *p, uintptr_t a)
     return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
 }
 
+// Kernel launch that first drops whatever error an earlier, unrelated HIP call of
+// this thread left behind (HIP keeps the last error per thread until it is read, so
+// a failed query made by the caller's framework would otherwise be reported as ours).
+#define MQ_LAUNCH(...)                      \
+    do {                                    \
+        (void)hipGetLastError();            \
+        hipLaunchKernelGGL(__VA_ARGS__);    \
+    } while (0)
+
+// Status of the launch just made.  With MQUANT_DEBUG set in the environment the
+// HIP error text goes to stderr as well (the C-ABI carries only the status code).
 static inline int launch_status()
 {
-    return hipGetLastError() == hipSuccess ? MQUANT_OK : MQUANT_ERR_HIP;
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return MQUANT_OK;
+    if (getenv("MQUANT_DEBUG")) fprintf(stderr, "mquant: HIP error %d: %s\n", (int)e, hipGetErrorString(e));
+    return MQUANT_ERR_HIP;
 }
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -178,7 +178,7 @@ __device__ __forceinline__ void tile_of_group(int32_t id, int32_t tiles_m, int32
 }
 
 template <int BM, int BN, int WM, int WN, int STAGES>
-__global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
+__global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_kernel(
     const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
     __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
     int32_t K, int32_t n_vis, float s_vis, float s_txt, int32_t tiles_m, int32_t tiles_n,
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
     constexpr int CH = (A_CH + B_CH) / NW;            // ... per wave
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "tile shape");
     static_assert((A_CH + B_CH) % NW == 0, "chunks must divide evenly over the waves");
-    static_assert(STAGES >= 2 && CH * (STAGES - 2) < 64, "pipeline depth");
+    static_assert((STAGES == 2 || STAGES == 3) && CH * (STAGES - 1) < 64, "pipeline depth");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
@@ -251,60 +251,142 @@ __global__ __launch_bounds__(WM *WN * 64) void w4a8_gemm_kernel(
             src_step[j] = 2 * kPackTileBytes;
         }
     }
-    auto load_stage = [&](int32_t kb, int buf) {
-#pragma unroll
-        for (int j = 0; j < CH; ++j)
-            lds_dma16(src[j] + static_cast<int64_t>(kb) * src_step[j],
-                      smem + buf * STAGE + (wave + j * NW) * 1024);
+    // DMA chunk j of this wave for k-block kb (relative to kb0) into stage buffer buf.
+    auto dma_chunk = [&](int j, int32_t kb, int buf) {
+        lds_dma16(src[j] + static_cast<int64_t>(kb) * src_step[j],
+                  smem + buf * STAGE + (wave + j * NW) * 1024);
     };
-    auto compute = [&](int buf) {
+    // Fragment reads.  A k-block is consumed in four phases (ks, h) of 32 channels:
+    // phase (ks, h) multiplies 16-byte chunk ks*4 + g*2 + h of every A row with half h
+    // of the unpacked B tile of k-tile ks.
+    auto read_a = [&](int buf, int ks, int h, v4i (&dst)[MT]) {
         const uint8_t *abase = smem + buf * STAGE;
-        const uint8_t *bbase = abase + A_STAGE;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            v4i a[MT][2], b[NT][2];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int r = wm * (BM / WM) + mt * 32 + l32;
-                const int c = ks * 4 + g * 2;
-                a[mt][0] = as_v4i(*reinterpret_cast<const uint4 *>(abase + lds_a_offset(r, c)));
-                a[mt][1] = as_v4i(*reinterpret_cast<const uint4 *>(abase + lds_a_offset(r, c + 1)));
-            }
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const uint4 p = *reinterpret_cast<const uint4 *>(
-                    bbase + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
-                unpack_w4x16(p, b[nt][0], b[nt][1]);
-            }
-            // consecutive MFMAs write different accumulators (a dependent pair
-            // back to back would wait out the full MFMA latency)
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                            a[mt][h], b[nt][h], acc[mt][nt], 0, 0, 0);
+        for (int mt = 0; mt < MT; ++mt) {
+            const int r = wm * (BM / WM) + mt * 32 + l32;
+            dst[mt] = as_v4i(*reinterpret_cast<const uint4 *>(
+                abase + lds_a_offset(r, ks * 4 + g * 2 + h)));
         }
     };
-
+    auto read_b = [&](int buf, int ks, uint4 (&dst)[NT]) {
+        const uint8_t *bbase = smem + buf * STAGE + A_STAGE;
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (s < k_blocks) load_stage(s, s);
+        for (int nt = 0; nt < NT; ++nt)
+            dst[nt] = *reinterpret_cast<const uint4 *>(
+                bbase + ((wn * NT + nt) * 2 + ks) * 1024 + lane * 16);
+    };
+    // One phase: MT*NT MFMAs (consecutive ones write different accumulators, a
+    // dependent pair back to back would wait out the full MFMA latency) with DMA
+    // chunks [j0, j0+nj) of a later stage issued between them.  Eight waves that
+    // issue a whole stage of LDS-DMA at once queue up behind the one texture
+    // address unit of the CU for hundreds of cycles with nothing else to issue.
+    auto phase = [&](const v4i (&a)[MT], const v4i (&b)[NT][2], int h, int j0, int nj, bool dma_on,
+                     int32_t dma_kb, int dma_buf) {
+        int issued = 0, j = 0;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt], b[nt][h], acc[mt][nt],
+                                                                    0, 0, 0);
+                ++issued;
+                if (j < nj && issued == ((j + 1) * (MT * NT) + nj) / (nj + 1)) {
+                    if (dma_on) dma_chunk(j0 + j, dma_kb, dma_buf);
+                    ++j;
+                }
+            }
+    };
+    // Chunks of one stage are spread over three phases.
+    constexpr int C_P3 = (CH + 2) / 3, C_P0 = (CH + 1) / 3, C_P1 = CH - C_P3 - C_P0;
+    static_assert(C_P3 <= MT * NT, "more DMA chunks than MFMAs in a phase");
 
-    int buf = 0, nbuf = STAGES - 1;
+    if constexpr (STAGES == 2) {
+        // Two work-groups share a CU (four waves per SIMD): the other group's waves
+        // fill every stall of this one, and the plain order -- wait, barrier, whole
+        // next stage, all fragments, all MFMAs -- with its lower register count is
+        // the faster one (measured 32.5 us against 35.2 us on 1280 x 3584 x 4608).
+        if (k_blocks > 0)
+#pragma unroll
+            for (int j = 0; j < CH; ++j) dma_chunk(j, 0, 0);
+        for (int32_t kb = 0; kb < k_blocks; ++kb) {
+            const int buf = kb & 1;
+            wait_vmcnt<0>();
+            // After the barrier every wave sees stage kb and has finished reading
+            // stage kb-1, whose buffer the next DMA overwrites.
+            __syncthreads();
+            if (kb + 1 < k_blocks)
+#pragma unroll
+                for (int j = 0; j < CH; ++j) dma_chunk(j, kb + 1, buf ^ 1);
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                v4i a[2][MT], b[NT][2];
+                uint4 braw[NT];
+                read_a(buf, ks, 0, a[0]);
+                read_a(buf, ks, 1, a[1]);
+                read_b(buf, ks, braw);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) unpack_w4x16(braw[nt], b[nt][0], b[nt][1]);
+                phase(a[0], b, 0, 0, 0, false, 0, 0);
+                phase(a[1], b, 1, 0, 0, false, 0, 0);
+            }
+        }
+    } else {
+    // ---- prologue: fill every stage buffer, wait for stage 0, first fragments
+#pragma unroll
+    for (int s = 0; s < STAGES; ++s)
+        if (s < k_blocks)
+#pragma unroll
+            for (int j = 0; j < CH; ++j) dma_chunk(j, s, s);
+    if (k_blocks >= 3) wait_vmcnt<2 * CH>();
+    else if (k_blocks == 2) wait_vmcnt<CH>();
+    else wait_vmcnt<0>();
+    __syncthreads();
+
+    v4i afr[2][MT];              // A fragments of the current and the next phase
+    uint4 braw[2][NT];           // packed B tiles of k-tile 0 and 1
+    read_a(0, 0, 0, afr[0]);
+    read_b(0, 0, braw[0]);
+
+    // ---- main loop.  Every phase first requests the fragments of the next one,
+    // so LDS latency hides under a phase's MFMAs; the barrier sits before phase 3,
+    // whose operands are already in registers, and phase 3 requests the first
+    // fragments of the next k-block from the buffer the barrier has just published.
+    // After barrier kb every wave has finished reading buffer kb % STAGES (its
+    // last reads were requested in phase 2), so stage kb + STAGES may overwrite it.
+    int buf = 0;
     for (int32_t kb = 0; kb < k_blocks; ++kb) {
-        // Stage kb must have landed; the STAGES-2 younger stages may stay in flight.
-        if (kb + STAGES - 2 < k_blocks) wait_vmcnt<CH * (STAGES - 2)>();
+        const int nb = buf + 1 == STAGES ? 0 : buf + 1;        // buffer of k-block kb + 1
+        const int pb = buf == 0 ? STAGES - 1 : buf - 1;        // buffer of kb - 1: stage kb-1+STAGES
+        const bool refill_p = kb >= 1 && kb - 1 + STAGES < k_blocks;
+        const bool refill_c = kb + STAGES < k_blocks;
+        v4i b0[NT][2], b1[NT][2];
+
+        read_a(buf, 0, 1, afr[1]);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) unpack_w4x16(braw[0][nt], b0[nt][0], b0[nt][1]);
+        phase(afr[0], b0, 0, C_P3, C_P0, refill_p, kb - 1 + STAGES, pb);
+
+        read_a(buf, 1, 0, afr[0]);
+        read_b(buf, 1, braw[1]);
+        phase(afr[1], b0, 1, C_P3 + C_P0, C_P1, refill_p, kb - 1 + STAGES, pb);
+
+        read_a(buf, 1, 1, afr[1]);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) unpack_w4x16(braw[1][nt], b1[nt][0], b1[nt][1]);
+        phase(afr[0], b1, 0, 0, 0, false, 0, 0);
+
+        // Stage kb+1 must have landed; stage kb+2 may stay in flight.
+        if (kb + 2 < k_blocks) wait_vmcnt<CH>();
         else wait_vmcnt<0>();
-        // After the barrier every wave sees stage kb and has finished reading
-        // stage kb-1, whose buffer the next DMA overwrites.
         __syncthreads();
-        if (kb + STAGES - 1 < k_blocks) load_stage(kb + STAGES - 1, nbuf);
-        compute(buf);
-        buf = buf + 1 == STAGES ? 0 : buf + 1;
-        nbuf = nbuf + 1 == STAGES ? 0 : nbuf + 1;
+
+        if (kb + 1 < k_blocks) {
+            read_a(nb, 0, 0, afr[0]);
+            read_b(nb, 0, braw[0]);
+        }
+        phase(afr[1], b1, 1, 0, C_P3, refill_c, kb + STAGES, buf);
+        buf = nb;
+    }
     }
 
     const int32_t wave_row0 = row0 + wm * (BM / WM);
@@ -597,7 +679,7 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
             return MQUANT_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(WM * WN * 64), lds, stream, xq,
+    MQ_LAUNCH(kern, dim3(tiles_m * tiles_n * splits), dim3(WM * WN * 64), lds, stream, xq,
                        reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
                        static_cast<__half *>(y), ldy, acc_out, T, N, K, n_vis, s_vis, s_txt,
                        tiles_m, tiles_n, n_tiles32, splits, kb_per_split,
@@ -607,7 +689,7 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
     const int64_t quads = static_cast<int64_t>(T) * (N / 4);
     int64_t blocks = ceil_div(quads, 256);
     if (blocks > 8 * kNumCU) blocks = 8 * kNumCU;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
+    MQ_LAUNCH(splitk_reduce_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
                        stream, partial, splits, T, N, static_cast<const __half *>(w_scale),
                        static_cast<__half *>(y), ldy, acc_out, n_vis, s_vis, s_txt);
     return launch_status();
@@ -649,7 +731,7 @@ extern "C" int mquant_w4_prepack(const uint8_t *w, uint8_t *out, int32_t N, int3
     const int64_t dwords = static_cast<int64_t>(n_tiles) * k_tiles * 256;
     int64_t blocks = ceil_div(dwords, 256);
     if (blocks > (1 << 20)) blocks = 1 << 20;
-    hipLaunchKernelGGL(prepack_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
+    MQ_LAUNCH(prepack_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), w, reinterpret_cast<uint32_t *>(out), N, K,
                        n_tiles, k_tiles);
     return launch_status();
@@ -687,12 +769,12 @@ extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void 
             int32_t *as = acc_out ? acc_out + static_cast<int64_t>(t0) * N : nullptr;
             // Few n-tiles: more waves per tile to keep enough loads in flight.
             if (n_tiles >= 256)
-                hipLaunchKernelGGL((w4a8_gemv_kernel<8, 4>), dim3(n_tiles), dim3(512), 0, stream, xs,
+                MQ_LAUNCH((w4a8_gemv_kernel<8, 4>), dim3(n_tiles), dim3(512), 0, stream, xs,
                                    reinterpret_cast<const uint4 *>(wp),
                                    static_cast<const __half *>(w_scale), ys, ldy, as, tt, N, K, nv,
                                    s_vis, s_txt);
             else
-                hipLaunchKernelGGL((w4a8_gemv_kernel<16, 4>), dim3(n_tiles), dim3(1024), 0, stream,
+                MQ_LAUNCH((w4a8_gemv_kernel<16, 4>), dim3(n_tiles), dim3(1024), 0, stream,
                                    xs, reinterpret_cast<const uint4 *>(wp),
                                    static_cast<const __half *>(w_scale), ys, ldy, as, tt, N, K, nv,
                                    s_vis, s_txt);
