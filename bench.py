@@ -333,7 +333,57 @@ def bench_decode(args, torch, mq, wl):
                          "frac": round(gbps / HBM_PEAK_GBPS, 4)}
         res["bytes_per_layer"] = bytes_layer
         out["per_T"][f"T{T}"] = res
+    del layers, fused_layers
+    out["large_shapes_T1"] = bench_decode_large(args, torch, mq, wl, gen)
     return out
+
+
+def bench_decode_large(args, torch, mq, wl, gen):
+    """The same GEMV on the 72B-class shapes of configs[4] at T=1 (context: on the 7B shapes a
+    launch streams for 1-10 us and launch latency is a large share; here a launch streams 30-240
+    MB).  Six distinct layers (2.6 GB) defeat the last-level cache; one HIP graph per pass."""
+    w4 = wl.workload(4, 1)
+    n_layers = 6
+    layers = []
+    for _ in range(n_layers):
+        layer = {}
+        for proj, (K, N) in w4.projections.items():
+            nbytes = mq.w4_prepacked_bytes(N, K)
+            wp = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda", generator=gen)
+            ws = (torch.rand(N, device="cuda", generator=gen) * 0.015 + 0.005).half()
+            layer[proj] = (K, N, wp, ws)
+        layers.append(layer)
+    Ks = sorted({K for (K, N) in w4.projections.values()})
+    xq = {K: torch.randint(-128, 128, (1, K), dtype=torch.int8, device="cuda", generator=gen) for K in Ks}
+    ys = {N: torch.empty((1, N), dtype=torch.float16, device="cuda") for (K, N) in w4.projections.values()}
+
+    def one_pass():
+        for layer in layers:
+            for proj, (K, N, wp, ws) in layer.items():
+                mq.w4a8_gemm(xq[K], wp, ws, N, 0, 0.035, 0.035, out=ys[N])
+
+    one_pass()
+    torch.cuda.synchronize()
+    if args.no_graphs:
+        run = one_pass
+    else:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one_pass()
+        run = graph.replay
+        run()
+        torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.decode_iters):
+        run()
+    torch.cuda.synchronize()
+    ms_layer = (time.perf_counter() - t0) * 1e3 / args.decode_iters / n_layers
+    bytes_layer = sum(K * N / 2 + 2 * N + K + 2 * N for (K, N) in w4.projections.values())
+    gbps = bytes_layer / (ms_layer * 1e-3) / 1e9
+    return {"workload": "configs[4] projections (qkv 8192x10240, o 8192x8192, gate_up 8192x59136, "
+                        "down 29568x8192), T=1, %d layers" % n_layers,
+            "us_per_layer": round(ms_layer * 1e3, 2), "bytes_per_layer": bytes_layer,
+            "GBps": round(gbps, 1), "frac": round(gbps / HBM_PEAK_GBPS, 4)}
 
 
 def cpu_baseline(args, np, w, lin, V):
