@@ -11,6 +11,8 @@
  *   - modality-specific static scales (MSQ) ......... Sec. 3.1, Eq. (3)
  *   - Walsh-Hadamard matrix H_{2^n} = H_2 (x) H_{2^{n-1}}  Appendix "Weights
  *     Outliers after Online Hadamard Transformation"
+ *   - per-token dynamic quantization (baseline) ...... Sec. 2.2, appendix on
+ *     quantization granularity
  *   - W4A8 integer GEMM with per-channel weight scale and per-modality
  *     activation scale ................................ Sec. 4 (Table 3 text,
  *     "Speedup" paragraphs)
@@ -96,6 +98,58 @@ void orc_msq_quantize(const float *u, int64_t T, int64_t K, int64_t V,
             if (r < -128.0f) r = -128.0f;
             if (r > 127.0f) r = 127.0f;
             xq[i * K + k] = (int8_t)r;
+        }
+    }
+}
+
+/*
+ * Per-token dynamic quantization (Sec. 2.2: the scale of Eq. (2) taken from
+ * runtime statistics; appendix on quantization granularity: one scale per
+ * token).  The comparison baseline of the speed tables, not MQuant's own path.
+ * For every row i of the unnormalised rotation u:
+ *     a_i = max_k |u[i,k]|
+ *     s_i = fp32( a_i / sqrt(B) / 127 )            Eq. (2): max|x| / (2^{b-1}-1)
+ *     c_i = fp32( 1 / (s_i sqrt(B)) )              same folding as the static path
+ *     xq[i,k] = clamp(rne(u[i,k] * c_i), -128, 127)
+ * both scalars evaluated in double and rounded once.  The paper does not say
+ * what an all-zero token gets: here s_i = 1 and every code is 0.
+ */
+void orc_dyn_quantize(const float *u, int64_t T, int64_t K, double sqrt_b,
+                      int8_t *xq, float *s_rows)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < T; ++i) {
+        float a = 0.0f;
+        for (int64_t k = 0; k < K; ++k) {
+            float v = fabsf(u[i * K + k]);
+            if (v > a) a = v;
+        }
+        float s = 1.0f, c = 1.0f;
+        if (a > 0.0f) {
+            s = (float)((double)a / sqrt_b / 127.0);
+            c = (float)(1.0 / ((double)s * sqrt_b));
+        }
+        s_rows[i] = s;
+        for (int64_t k = 0; k < K; ++k) {
+            float t = u[i * K + k] * c;
+            float r = nearbyintf(t);
+            if (r < -128.0f) r = -128.0f;
+            if (r > 127.0f) r = 127.0f;
+            xq[i * K + k] = (int8_t)r;
+        }
+    }
+}
+
+/* Dequantisation with one activation scale per token ("per token scale" of the
+ * scheme-comparison table): ref[i,n] = (float(acc[i,n]) * s_rows[i]) * w_scale[n]. */
+void orc_dequant_rows_f32(const int32_t *acc, int64_t T, int64_t N,
+                          const float *s_rows, const float *w_scale, float *ref)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < T; ++i) {
+        for (int64_t n = 0; n < N; ++n) {
+            float a = (float)acc[i * N + n];
+            ref[i * N + n] = (a * s_rows[i]) * w_scale[n];
         }
     }
 }

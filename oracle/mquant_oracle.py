@@ -48,6 +48,8 @@ def _lib() -> ctypes.CDLL:
         lib.orc_unpack_w4.argtypes = [p, i64, i64, p]
         lib.orc_gemm_i8_i4_i32.argtypes = [p, p, i64, i64, i64, p]
         lib.orc_dequant_f32.argtypes = [p, i64, i64, i64, f32, f32, p, p]
+        lib.orc_dyn_quantize.argtypes = [p, i64, i64, ctypes.c_double, p, p]
+        lib.orc_dequant_rows_f32.argtypes = [p, i64, i64, p, p, p]
         _LIB = lib
     return _LIB
 
@@ -263,6 +265,46 @@ def dequant(acc: np.ndarray, V: int, s_vis: float, s_txt: float, w_scale: np.nda
     _lib().orc_dequant_f32(_ptr(acc), T, N, V, np.float32(s_vis), np.float32(s_txt),
                            _ptr(ws), _ptr(ref))
     return ref, ref.astype(np.float16)
+
+
+def dyn_quantize(u: np.ndarray, B: int):
+    """Per-token dynamic int8 quantization of the unnormalised rotation u
+    (Sec. 2.2 "dynamic quantization"; one scale per token as in the appendix on
+    granularity): returns (codes int8 [T,K], s fp32 [T]) with
+    s_i = fp32(max_k|u_ik| / sqrt(B) / 127); an all-zero row gets s_i = 1."""
+    u = _c(u, np.float32)
+    T, K = u.shape
+    xq = np.empty((T, K), dtype=np.int8)
+    s_rows = np.empty(T, dtype=np.float32)
+    _lib().orc_dyn_quantize(_ptr(u), T, K, math.sqrt(float(B)), _ptr(xq), _ptr(s_rows))
+    return xq, s_rows
+
+
+def dequant_rows(acc: np.ndarray, s_rows: np.ndarray, w_scale: np.ndarray):
+    """(fp32 reference, fp16 output): ref = (float(acc) s_i) w_scale[n], s_i per token."""
+    acc = _c(acc, np.int32)
+    T, N = acc.shape
+    ws = _c(np.asarray(w_scale).astype(np.float32), np.float32)
+    sr = _c(s_rows, np.float32)
+    assert sr.shape == (T,)
+    ref = np.empty((T, N), dtype=np.float32)
+    _lib().orc_dequant_rows_f32(_ptr(acc), T, N, _ptr(sr), _ptr(ws), _ptr(ref))
+    return ref, ref.astype(np.float16)
+
+
+def w4a8_linear_dynamic(x_u: np.ndarray, w_packed: np.ndarray, w_scale: np.ndarray, B: int,
+                        rows=None, cols=None) -> dict:
+    """The per-token dynamic baseline on one linear: rotate, per-row scale and
+    codes, integer GEMM, per-row dequant.  x_u is fp16 [T, K] (row order is
+    irrelevant to this scheme: every row carries its own scale)."""
+    u = hadamard_rotate(x_u, B)
+    xq, s_rows = dyn_quantize(u, B)
+    xs, sr = (xq, s_rows) if rows is None else (xq[np.asarray(rows)], s_rows[np.asarray(rows)])
+    wp = w_packed if cols is None else w_packed[np.asarray(cols)]
+    ws = w_scale if cols is None else np.asarray(w_scale)[np.asarray(cols)]
+    acc = gemm_i8_i4_i32(xs, unpack_w4(wp))
+    ref, y = dequant_rows(acc, sr, ws)
+    return {"xq": xq, "s_rows": s_rows, "acc": acc, "ref": ref, "y": y}
 
 
 def w4a8_linear(x: np.ndarray, vis_spans: Sequence[Tuple[int, int]], w_packed: np.ndarray,
