@@ -148,6 +148,23 @@ int mquant_hadamard_quant_act(const void *x_dev, int64_t ldx, const int32_t *per
 int mquant_hadamard_absmax(const void *x_dev, int64_t ldx, int32_t T, int32_t K,
                            int32_t had_block, float *absmax_dev, mquant_stream_t stream);
 
+/*
+ * DEVICE.  Per-token dynamic activation quantization, the baseline the speed
+ * tables of Sec. 4 compare MSQ against (Sec. 2.2: the scale of Eq. (2) from
+ * runtime statistics; appendix on quantization granularity: one scale per
+ * token).  Same rotation as mquant_hadamard_quant_act; for every row i
+ *   s_i = fp32( max_k |x_rot[i,k]| / 127 ),  xq[i,:] = clamp(rne(x_rot[i,:] / s_i)),
+ * an all-zero row gets s_i = 1.  Nothing of a row can be written before the
+ * whole row has been read and reduced, which is the cost static scales avoid.
+ *   row_scale_dev : fp32 [T] (written), 4-byte aligned
+ *   other arguments as in mquant_hadamard_quant_act.
+ * Errors: as mquant_hadamard_quant_act; ERR_UNSUPPORTED also when a row does
+ *         not fit the registers of one work-group (K > 32768).
+ */
+int mquant_hadamard_dynquant_act(const void *x_dev, int64_t ldx, const int32_t *perm_dev,
+                                 int8_t *xq_dev, float *row_scale_dev, int32_t T, int32_t K,
+                                 int32_t had_block, mquant_stream_t stream);
+
 /* -------------------------------------------------------------------------
  * W4A8 GEMM / GEMV (Sec. 4: "W4A8 GEMM", "custom W4A8 GEMV kernel") with the
  * fused dequantisation y = acc * s_row * s_w[n].
@@ -171,7 +188,8 @@ int64_t mquant_w4_prepacked_bytes(int32_t N, int32_t K);
 int mquant_w4_prepack(const uint8_t *w_canonical_dev, uint8_t *w_prepacked_dev,
                       int32_t N, int32_t K, mquant_stream_t stream);
 
-/* Workspace mquant_w4a8_gemm needs for this shape (may be 0). */
+/* Workspace mquant_w4a8_gemm needs for this shape: 0 except for long-K shapes with few
+ * output tiles, which are computed as split-K partial sums (splits * T * N * 4 bytes). */
 int64_t mquant_w4a8_workspace_bytes(int32_t T, int32_t N, int32_t K);
 
 /*
@@ -195,6 +213,20 @@ int mquant_w4a8_gemm(const int8_t *xq_dev, const uint8_t *w_prepacked_dev,
                      const void *w_scale_dev, void *y_dev, int64_t ldy, int32_t *acc_out_dev,
                      int32_t T, int32_t N, int32_t K, int32_t n_vis, float s_vis, float s_txt,
                      void *workspace_dev, int64_t workspace_bytes, mquant_stream_t stream);
+
+/*
+ * DEVICE.  The same GEMM / GEMV with one activation scale per token
+ * ("per token scale" of the scheme-comparison table in Sec. 4):
+ * y[i, n] = fp16( (float(acc[i, n]) * row_scale[i]) * float(w_scale[n]) ).
+ *   row_scale_dev : fp32 [T], e.g. from mquant_hadamard_dynquant_act
+ * Other arguments, workspace (mquant_w4a8_workspace_bytes) and errors as in
+ * mquant_w4a8_gemm.
+ */
+int mquant_w4a8_gemm_rowscale(const int8_t *xq_dev, const uint8_t *w_prepacked_dev,
+                              const void *w_scale_dev, const float *row_scale_dev, void *y_dev,
+                              int64_t ldy, int32_t *acc_out_dev, int32_t T, int32_t N, int32_t K,
+                              void *workspace_dev, int64_t workspace_bytes,
+                              mquant_stream_t stream);
 
 /* Workspace of the fused prefill entry: the int8 activations plus whatever
  * mquant_w4a8_gemm needs. */

@@ -27,6 +27,7 @@ EXPORTS = (
     "mquant_aifs_remap_mask", "mquant_hadamard_quant_act", "mquant_hadamard_absmax",
     "mquant_w4_prepacked_bytes", "mquant_w4_prepack", "mquant_w4a8_workspace_bytes",
     "mquant_w4a8_gemm", "mquant_w4a8_linear_prefill_workspace_bytes", "mquant_w4a8_linear_prefill",
+    "mquant_hadamard_dynquant_act", "mquant_w4a8_gemm_rowscale",
 )
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGNMENT = 0, -1, -2, -3, -4, -5, -6
@@ -57,6 +58,8 @@ def _load() -> ctypes.CDLL:
     lib.mquant_aifs_remap_mask.argtypes = [p, p, p, i32, p]
     lib.mquant_hadamard_quant_act.argtypes = [p, i64, p, p, i32, i32, i32, f32, f32, i32, p]
     lib.mquant_hadamard_absmax.argtypes = [p, i64, i32, i32, i32, p, p]
+    lib.mquant_hadamard_dynquant_act.argtypes = [p, i64, p, p, p, i32, i32, i32, p]
+    lib.mquant_w4a8_gemm_rowscale.argtypes = [p, p, p, p, p, i64, p, i32, i32, i32, p, i64, p]
     lib.mquant_w4_prepacked_bytes.restype = i64
     lib.mquant_w4_prepacked_bytes.argtypes = [i32, i32]
     lib.mquant_w4_prepack.argtypes = [p, p, i32, i32, p]
@@ -199,6 +202,37 @@ def w4a8_gemm(xq, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float, s_txt:
     _check(lib.mquant_w4a8_gemm(_dp(xq), _dp(w_prepacked), _dp(w_scale), _dp(out), out.stride(0),
                                 _dp(acc_out), T, N, K, n_vis, s_vis, s_txt, _dp(workspace),
                                 ws_bytes, _stream()), "mquant_w4a8_gemm")
+    return out
+
+
+def hadamard_dynquant_act(x, had_block: int, perm_dev=None, out=None, row_scale=None):
+    import torch
+    T, K = x.shape
+    if out is None:
+        out = torch.empty((T, K), dtype=torch.int8, device=x.device)
+    if row_scale is None:
+        row_scale = torch.empty((T,), dtype=torch.float32, device=x.device)
+    _check(lib.mquant_hadamard_dynquant_act(_dp(x), x.stride(0), _dp(perm_dev), _dp(out),
+                                            _dp(row_scale), T, K, had_block, _stream()),
+           "mquant_hadamard_dynquant_act")
+    return out, row_scale
+
+
+def w4a8_gemm_rowscale(xq, w_prepacked, w_scale, row_scale, N: int, out=None, acc_out=None,
+                       workspace=None):
+    import torch
+    T, K = xq.shape
+    if out is None:
+        out = torch.empty((T, N), dtype=torch.float16, device=xq.device)
+    if workspace is None:
+        need = w4a8_workspace_bytes(T, N, K)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=xq.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.mquant_w4a8_gemm_rowscale(_dp(xq), _dp(w_prepacked), _dp(w_scale), _dp(row_scale),
+                                         _dp(out), out.stride(0), _dp(acc_out), T, N, K,
+                                         _dp(workspace), ws_bytes, _stream()),
+           "mquant_w4a8_gemm_rowscale")
     return out
 
 

@@ -125,31 +125,17 @@ __device__ __forceinline__ void lane_stages(float (&v)[8], int lane)
     lane_stage<B, 32>(v, lane);
 }
 
-template <int B, bool ABSMAX>
-__global__ __launch_bounds__(256) void hadamard_quant_kernel(
-    const __half *__restrict__ x, int64_t ldx, const int32_t *__restrict__ perm,
-    int8_t *__restrict__ xq, int32_t T, int32_t K, int32_t n_vis, float c_vis, float c_txt,
-    int32_t segs_per_row, float *__restrict__ absmax)
-{
-    constexpr int C = B > 512 ? B / 512 : 1;      // 512-channel chunks per wave segment
-    constexpr int SEG = 512 * C;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t wave0 = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    const int64_t total = static_cast<int64_t>(T) * segs_per_row;
-    float wave_max = 0.0f;
+// One wave segment: SEG = max(B, 512) consecutive channels of one row, C = SEG/512
+// chunks of 512, 8 channels per lane and chunk.  Loads fp16, rotates in fp32.
+template <int B>
+struct Segment {
+    static constexpr int C = B > 512 ? B / 512 : 1;
+    static constexpr int SEG = 512 * C;
+    float v[C][8];
+    bool valid[C];
 
-    for (int64_t seg = wave0; seg < total; seg += static_cast<int64_t>(gridDim.x) * 4) {
-        const int32_t i = static_cast<int32_t>(seg / segs_per_row);
-        const int32_t sidx = static_cast<int32_t>(seg - static_cast<int64_t>(i) * segs_per_row);
-        int32_t src = i;
-        if (perm != nullptr) {
-            src = perm[i];
-            src = (src < 0 || src >= T) ? 0 : src;
-        }
-        const __half *row = x + static_cast<int64_t>(src) * ldx;
-
-        float v[C][8];
-        bool valid[C];
+    __device__ __forceinline__ void load_rotate(const __half *row, int32_t sidx, int32_t K, int lane)
+    {
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             const int32_t k0 = sidx * SEG + c * 512 + lane * 8;
@@ -168,7 +154,6 @@ __global__ __launch_bounds__(256) void hadamard_quant_kernel(
                 for (int j = 0; j < 8; ++j) v[c][j] = 0.0f;
             }
         }
-
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             register_stages<B>(v[c]);
@@ -189,42 +174,75 @@ __global__ __launch_bounds__(256) void hadamard_quant_kernel(
                 }
             }
         }
+    }
 
+    __device__ __forceinline__ float absmax(float m) const
+    {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            if (valid[c]) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(v[c][j]));
+            }
+        }
+        return m;
+    }
+
+    // int8 codes clamp(rne(v * cmul)) of this segment into row `xq_row`.
+    __device__ __forceinline__ void quant_store(float cmul, int8_t *xq_row, int32_t sidx, int lane) const
+    {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            if (valid[c]) {
+                // clamp(rint(t)) == rint(clamp(t)) for integer bounds; adding 1.5 * 2^23
+                // rounds to an integer (ties to even) and leaves it in the low mantissa
+                // bits, whose low byte is the two's-complement int8 code.
+                uint32_t bits[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float t = __builtin_amdgcn_fmed3f(v[c][j] * cmul, -128.0f, 127.0f);
+                    bits[j] = __float_as_uint(t + 12582912.0f);
+                }
+                uint32_t packed[2];
+#pragma unroll
+                for (int w = 0; w < 2; ++w) {
+                    // byte 0 of four words -> one dword
+                    const uint32_t p01 = __builtin_amdgcn_perm(bits[4 * w + 1], bits[4 * w], 0x0c0c0400u);
+                    const uint32_t p23 = __builtin_amdgcn_perm(bits[4 * w + 3], bits[4 * w + 2], 0x04000c0cu);
+                    packed[w] = p01 | p23;
+                }
+                const int64_t k0 = static_cast<int64_t>(sidx) * SEG + c * 512 + lane * 8;
+                *reinterpret_cast<uint2 *>(xq_row + k0) = make_uint2(packed[0], packed[1]);
+            }
+        }
+    }
+};
+
+template <int B, bool ABSMAX>
+__global__ __launch_bounds__(256) void hadamard_quant_kernel(
+    const __half *__restrict__ x, int64_t ldx, const int32_t *__restrict__ perm,
+    int8_t *__restrict__ xq, int32_t T, int32_t K, int32_t n_vis, float c_vis, float c_txt,
+    int32_t segs_per_row, float *__restrict__ absmax)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave0 = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int64_t total = static_cast<int64_t>(T) * segs_per_row;
+    float wave_max = 0.0f;
+
+    for (int64_t seg = wave0; seg < total; seg += static_cast<int64_t>(gridDim.x) * 4) {
+        const int32_t i = static_cast<int32_t>(seg / segs_per_row);
+        const int32_t sidx = static_cast<int32_t>(seg - static_cast<int64_t>(i) * segs_per_row);
+        int32_t src = i;
+        if (perm != nullptr) {
+            src = perm[i];
+            src = (src < 0 || src >= T) ? 0 : src;
+        }
+        Segment<B> sg;
+        sg.load_rotate(x + static_cast<int64_t>(src) * ldx, sidx, K, lane);
         if constexpr (ABSMAX) {
-#pragma unroll
-            for (int c = 0; c < C; ++c) {
-                if (valid[c]) {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) wave_max = fmaxf(wave_max, fabsf(v[c][j]));
-                }
-            }
+            wave_max = sg.absmax(wave_max);
         } else {
-            const float cmul = (i < n_vis) ? c_vis : c_txt;
-#pragma unroll
-            for (int c = 0; c < C; ++c) {
-                if (valid[c]) {
-                    // clamp(rint(t)) == rint(clamp(t)) for integer bounds; adding 1.5 * 2^23
-                    // rounds to an integer (ties to even) and leaves it in the low mantissa
-                    // bits, whose low byte is the two's-complement int8 code.
-                    uint32_t bits[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const float t = __builtin_amdgcn_fmed3f(v[c][j] * cmul, -128.0f, 127.0f);
-                        bits[j] = __float_as_uint(t + 12582912.0f);
-                    }
-                    uint32_t packed[2];
-#pragma unroll
-                    for (int w = 0; w < 2; ++w) {
-                        // byte 0 of four words -> one dword
-                        const uint32_t p01 = __builtin_amdgcn_perm(bits[4 * w + 1], bits[4 * w], 0x0c0c0400u);
-                        const uint32_t p23 = __builtin_amdgcn_perm(bits[4 * w + 3], bits[4 * w + 2], 0x04000c0cu);
-                        packed[w] = p01 | p23;
-                    }
-                    const int64_t k0 = static_cast<int64_t>(sidx) * SEG + c * 512 + lane * 8;
-                    *reinterpret_cast<uint2 *>(xq + static_cast<int64_t>(i) * K + k0) =
-                        make_uint2(packed[0], packed[1]);
-                }
-            }
+            sg.quant_store((i < n_vis) ? c_vis : c_txt, xq + static_cast<int64_t>(i) * K, sidx, lane);
         }
     }
 
@@ -233,6 +251,60 @@ __global__ __launch_bounds__(256) void hadamard_quant_kernel(
         for (int m = 32; m >= 1; m >>= 1) wave_max = fmaxf(wave_max, __shfl_xor(wave_max, m, kWave));
         // non-negative floats order like their bit patterns
         if (lane == 0) atomicMax(reinterpret_cast<unsigned int *>(absmax), __float_as_uint(wave_max));
+    }
+}
+
+// Per-token dynamic quantization (the baseline the paper's speed tables compare
+// against; Sec. 2.2 and the appendix on quantization granularity): one
+// work-group per token.  Its four waves rotate the token's segments and keep
+// them in registers (NS segments per wave), the row maximum meets in LDS, the
+// scale s_i = fp32(max / sqrt(B) / 127) and the multiplier fp32(1 / (s_i sqrt(B)))
+// are formed in double, and the codes are written from the registers: the token
+// is read once, like in the static kernel, but nothing can be stored before the
+// whole token has been seen.  An all-zero token gets s_i = 1.
+template <int B, int NS>
+__global__ __launch_bounds__(256) void hadamard_dynquant_kernel(
+    const __half *__restrict__ x, int64_t ldx, const int32_t *__restrict__ perm,
+    int8_t *__restrict__ xq, float *__restrict__ row_scale, int32_t T, int32_t K,
+    int32_t segs_per_row, double sqrt_b)
+{
+    __shared__ float wave_max[4];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    for (int32_t i = blockIdx.x; i < T; i += gridDim.x) {
+        int32_t src = i;
+        if (perm != nullptr) {
+            src = perm[i];
+            src = (src < 0 || src >= T) ? 0 : src;
+        }
+        const __half *row = x + static_cast<int64_t>(src) * ldx;
+        Segment<B> sg[NS];
+        float m = 0.0f;
+#pragma unroll
+        for (int q = 0; q < NS; ++q) {
+            const int32_t sidx = wave + 4 * q;
+            if (sidx < segs_per_row) {               // wave-uniform
+                sg[q].load_rotate(row, sidx, K, lane);
+                m = sg[q].absmax(m);
+            }
+        }
+#pragma unroll
+        for (int sh = 32; sh >= 1; sh >>= 1) m = fmaxf(m, __shfl_xor(m, sh, kWave));
+        if (lane == 0) wave_max[wave] = m;
+        __syncthreads();
+        const float a = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+        __syncthreads();                              // wave_max is reused by the next token
+        float s = 1.0f, cmul = 1.0f;
+        if (a > 0.0f) {
+            s = static_cast<float>(static_cast<double>(a) / sqrt_b / 127.0);
+            cmul = static_cast<float>(1.0 / (static_cast<double>(s) * sqrt_b));
+        }
+        if (threadIdx.x == 0) row_scale[i] = s;
+#pragma unroll
+        for (int q = 0; q < NS; ++q) {
+            const int32_t sidx = wave + 4 * q;
+            if (sidx < segs_per_row) sg[q].quant_store(cmul, xq + static_cast<int64_t>(i) * K, sidx, lane);
+        }
     }
 }
 
@@ -305,4 +377,48 @@ extern "C" int mquant_hadamard_absmax(const void *x, int64_t ldx, int32_t T, int
     if (!absmax) return MQUANT_ERR_NULL;
     return launch<true>(x, ldx, nullptr, nullptr, T, K, 0, 0.0f, 0.0f, had_block, absmax,
                         static_cast<hipStream_t>(stream));
+}
+
+extern "C" int mquant_hadamard_dynquant_act(const void *x, int64_t ldx, const int32_t *perm,
+                                            int8_t *xq, float *row_scale, int32_t T, int32_t K,
+                                            int32_t had_block, mquant_stream_t stream)
+{
+    const int st = check_common(x, ldx, T, K, had_block);
+    if (st != MQUANT_OK) return st;
+    if (T == 0 || K == 0) return MQUANT_OK;
+    if (!xq || !row_scale) return MQUANT_ERR_NULL;
+    if (!aligned_to(xq, 8) || !aligned_to(row_scale, 4)) return MQUANT_ERR_ALIGNMENT;
+    const int32_t seg = had_block > 512 ? had_block : 512;
+    const int32_t segs_per_row = static_cast<int32_t>(ceil_div(K, seg));
+    const int32_t per_wave = static_cast<int32_t>(ceil_div(segs_per_row, 4));
+    if (per_wave > 16) return MQUANT_ERR_UNSUPPORTED;     // a token must fit the registers of a group
+    const dim3 grid(static_cast<unsigned>(T < (1 << 20) ? T : (1 << 20))), block(256);
+    const __half *xh = static_cast<const __half *>(x);
+    const double sqrt_b = sqrt(static_cast<double>(had_block));
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+#define MQ_CASE(BV)                                                                              \
+    case BV:                                                                                     \
+        if (per_wave <= 4)                                                                       \
+            MQ_LAUNCH((hadamard_dynquant_kernel<BV, 4>), grid, block, 0, hs, xh, ldx, perm, xq,  \
+                      row_scale, T, K, segs_per_row, sqrt_b);                                    \
+        else                                                                                     \
+            MQ_LAUNCH((hadamard_dynquant_kernel<BV, 16>), grid, block, 0, hs, xh, ldx, perm, xq, \
+                      row_scale, T, K, segs_per_row, sqrt_b);                                    \
+        break;
+    switch (had_block) {
+        MQ_CASE(1) MQ_CASE(2) MQ_CASE(4) MQ_CASE(8) MQ_CASE(16) MQ_CASE(32) MQ_CASE(64)
+        MQ_CASE(128) MQ_CASE(256) MQ_CASE(512)
+    case 1024:                       // two chunks per segment: half as many segments fit
+        if (per_wave > 8) return MQUANT_ERR_UNSUPPORTED;
+        if (per_wave <= 2)
+            MQ_LAUNCH((hadamard_dynquant_kernel<1024, 2>), grid, block, 0, hs, xh, ldx, perm, xq,
+                      row_scale, T, K, segs_per_row, sqrt_b);
+        else
+            MQ_LAUNCH((hadamard_dynquant_kernel<1024, 8>), grid, block, 0, hs, xh, ldx, perm, xq,
+                      row_scale, T, K, segs_per_row, sqrt_b);
+        break;
+    default: return MQUANT_ERR_UNSUPPORTED;
+    }
+#undef MQ_CASE
+    return launch_status();
 }

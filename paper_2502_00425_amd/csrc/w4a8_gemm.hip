@@ -94,6 +94,18 @@ __device__ __forceinline__ v4i as_v4i(const uint4 u)
 // Row of the 32x32 MFMA result held in accumulator register r by k-group g.
 __device__ __forceinline__ int acc_row(int r, int g) { return (r >> 2) * 8 + g * 4 + (r & 3); }
 
+// Activation scale of a row: the two static modality scales split at row n_vis
+// (Eq. (3)), or, for the per-token dynamic baseline, one scale per row.
+struct ActScale {
+    int32_t n_vis;
+    float s_vis, s_txt;
+    const float *rows;          // nullptr: static scales
+    __device__ __forceinline__ float of(int32_t row) const
+    {
+        return rows != nullptr ? rows[row] : (row < n_vis ? s_vis : s_txt);
+    }
+};
+
 __device__ __forceinline__ void store_out(int32_t acc16, int32_t row, int32_t n, float s_row,
                                           float ws, __half *y, int64_t ldy, int32_t *acc_out,
                                           int32_t N)
@@ -181,7 +193,7 @@ template <int BM, int BN, int WM, int WN, int STAGES>
 __global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_kernel(
     const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
     __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
-    int32_t K, int32_t n_vis, float s_vis, float s_txt, int32_t tiles_m, int32_t tiles_n,
+    int32_t K, ActScale as, int32_t tiles_m, int32_t tiles_n,
     int32_t n_tiles32, int32_t splits, int32_t kb_per_split, int32_t *__restrict__ partial,
     int32_t wide_store, int32_t band)
 {
@@ -424,7 +436,7 @@ __global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_ke
                 for (int r = 0; r < 16; ++r) {
                     const int32_t row = wave_row0 + mt * 32 + acc_row(r, g);
                     if (row < T) {
-                        const float s_row = row < n_vis ? s_vis : s_txt;
+                        const float s_row = as.of(row);
                         store_out(acc[mt][nt][r], row, n, s_row, ws, y, ldy, acc_out, N);
                     }
                 }
@@ -455,7 +467,7 @@ __global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_ke
         for (int r = 0; r < 16; ++r) {
             const int rl = acc_row(r, g);
             const int32_t row = wave_row0 + mt * 32 + rl;
-            const float s_row = row < n_vis ? s_vis : s_txt;
+            const float s_row = as.of(row);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 const int32_t a = acc[mt][nt][r] >> 4;             // exact: the sum holds 16 * acc
@@ -482,7 +494,7 @@ __global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_ke
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(
     const int32_t *__restrict__ partial, int32_t splits, int32_t T, int32_t N,
     const __half *__restrict__ w_scale, __half *__restrict__ y, int64_t ldy,
-    int32_t *__restrict__ acc_out, int32_t n_vis, float s_vis, float s_txt)
+    int32_t *__restrict__ acc_out, ActScale as)
 {
     const int64_t quads = static_cast<int64_t>(T) * (N / 4);
     const int64_t plane = static_cast<int64_t>(T) * N;
@@ -499,7 +511,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(
             sum.z += p.z;
             sum.w += p.w;
         }
-        const float s_row = row < n_vis ? s_vis : s_txt;
+        const float s_row = as.of(row);
         const int32_t a[4] = {sum.x >> 4, sum.y >> 4, sum.z >> 4, sum.w >> 4};
         __half h[4];
 #pragma unroll
@@ -530,7 +542,7 @@ template <int NWAVES, int KT>
 __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
     const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
     __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
-    int32_t K, int32_t n_vis, float s_vis, float s_txt)
+    int32_t K, ActScale as)
 {
     typedef unsigned int v4u __attribute__((ext_vector_type(4)));
     __shared__ int32_t red[NWAVES][16][64];
@@ -609,7 +621,7 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
             int32_t sum = 0;
 #pragma unroll
             for (int w = 0; w < NWAVES; ++w) sum += red[w][r][lane];
-            const float s_row = row < n_vis ? s_vis : s_txt;
+            const float s_row = as.of(row);
             store_out(sum, row, n, s_row, ws, y, ldy, acc_out, N);
         }
     }
@@ -656,8 +668,8 @@ int plan_splits(int32_t T, int32_t N, int32_t K)
 
 template <int BM, int BN, int WM, int WN, int STAGES>
 int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y, int64_t ldy,
-                int32_t *acc_out, int32_t T, int32_t N, int32_t K, int32_t n_vis, float s_vis,
-                float s_txt, int32_t splits, int32_t *partial, hipStream_t stream)
+                int32_t *acc_out, int32_t T, int32_t N, int32_t K, ActScale as, int32_t splits,
+                int32_t *partial, hipStream_t stream)
 {
     const int32_t tiles_m = static_cast<int32_t>(ceil_div(T, BM));
     const int32_t tiles_n = static_cast<int32_t>(ceil_div(N, BN));
@@ -681,8 +693,7 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
     }
     MQ_LAUNCH(kern, dim3(tiles_m * tiles_n * splits), dim3(WM * WN * 64), lds, stream, xq,
                        reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
-                       static_cast<__half *>(y), ldy, acc_out, T, N, K, n_vis, s_vis, s_txt,
-                       tiles_m, tiles_n, n_tiles32, splits, kb_per_split,
+                       static_cast<__half *>(y), ldy, acc_out, T, N, K, as, tiles_m, tiles_n, n_tiles32, splits, kb_per_split,
                        splits > 1 ? partial : nullptr, wide_store, band);
     int st = launch_status();
     if (st != MQUANT_OK || splits == 1) return st;
@@ -691,7 +702,7 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
     if (blocks > 8 * kNumCU) blocks = 8 * kNumCU;
     MQ_LAUNCH(splitk_reduce_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
                        stream, partial, splits, T, N, static_cast<const __half *>(w_scale),
-                       static_cast<__half *>(y), ldy, acc_out, n_vis, s_vis, s_txt);
+                       static_cast<__half *>(y), ldy, acc_out, as);
     return launch_status();
 }
 
@@ -746,38 +757,36 @@ extern "C" int64_t mquant_w4a8_workspace_bytes(int32_t T, int32_t N, int32_t K)
     return splits > 1 ? static_cast<int64_t>(splits) * T * N * 4 : 0;
 }
 
-extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y,
-                                int64_t ldy, int32_t *acc_out, int32_t T, int32_t N, int32_t K,
-                                int32_t n_vis, float s_vis, float s_txt, void *workspace,
-                                int64_t workspace_bytes, mquant_stream_t stream_)
-{
-    const int st = check_gemm_args(xq, wp, w_scale, y, ldy, T, N, K, n_vis, s_vis, s_txt);
-    if (st != MQUANT_OK) return st;
-    if (T == 0 || N == 0) return MQUANT_OK;
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
+namespace {
 
+// Shared body of the two GEMM entry points; `as` carries either the static or
+// the per-row activation scales.  Arguments are validated by the callers.
+int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y, int64_t ldy,
+                  int32_t *acc_out, int32_t T, int32_t N, int32_t K, ActScale as, void *workspace,
+                  int64_t workspace_bytes, hipStream_t stream)
+{
     if (T <= kGemvMaxT || K % 128 != 0) {
         // GEMV handles 32 rows per pass; walk taller inputs in slabs of 32 rows
         // (only reached for K % 128 != 0, which the prefill kernel does not take).
         for (int32_t t0 = 0; t0 < T; t0 += kGemvMaxT) {
             const int32_t tt = T - t0 < kGemvMaxT ? T - t0 : kGemvMaxT;
-            int32_t nv = n_vis - t0;
-            nv = nv < 0 ? 0 : (nv > tt ? tt : nv);
+            ActScale slab = as;
+            int32_t nv = as.n_vis - t0;
+            slab.n_vis = nv < 0 ? 0 : (nv > tt ? tt : nv);
+            if (as.rows != nullptr) slab.rows = as.rows + t0;
             const unsigned n_tiles = static_cast<unsigned>(ceil_div(N, 32));
             const int8_t *xs = xq + static_cast<int64_t>(t0) * K;
             __half *ys = static_cast<__half *>(y) + static_cast<int64_t>(t0) * ldy;
-            int32_t *as = acc_out ? acc_out + static_cast<int64_t>(t0) * N : nullptr;
+            int32_t *accs = acc_out ? acc_out + static_cast<int64_t>(t0) * N : nullptr;
             // Few n-tiles: more waves per tile to keep enough loads in flight.
             if (n_tiles >= 256)
                 MQ_LAUNCH((w4a8_gemv_kernel<8, 4>), dim3(n_tiles), dim3(512), 0, stream, xs,
-                                   reinterpret_cast<const uint4 *>(wp),
-                                   static_cast<const __half *>(w_scale), ys, ldy, as, tt, N, K, nv,
-                                   s_vis, s_txt);
+                          reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
+                          ys, ldy, accs, tt, N, K, slab);
             else
-                MQ_LAUNCH((w4a8_gemv_kernel<16, 4>), dim3(n_tiles), dim3(1024), 0, stream,
-                                   xs, reinterpret_cast<const uint4 *>(wp),
-                                   static_cast<const __half *>(w_scale), ys, ldy, as, tt, N, K, nv,
-                                   s_vis, s_txt);
+                MQ_LAUNCH((w4a8_gemv_kernel<16, 4>), dim3(n_tiles), dim3(1024), 0, stream, xs,
+                          reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
+                          ys, ldy, accs, tt, N, K, slab);
             const int ls = launch_status();
             if (ls != MQUANT_OK) return ls;
         }
@@ -791,15 +800,45 @@ extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void 
         const int64_t need = static_cast<int64_t>(splits) * T * N * 4;
         if (!workspace || workspace_bytes < need) return MQUANT_ERR_WORKSPACE;
         if (!aligned_to(workspace, 256)) return MQUANT_ERR_ALIGNMENT;
-        return launch_gemm<256, 256, 2, 4, 3>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
-                                                 s_vis, s_txt, splits,
+        return launch_gemm<256, 256, 2, 4, 3>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, as, splits,
                                                  static_cast<int32_t *>(workspace), stream);
     }
     if ((force_tile < 0 ? pick_gemm_tile(T, N) : force_tile) == 0)
-        return launch_gemm<256, 256, 2, 4, 3>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
-                                                 s_vis, s_txt, 1, nullptr, stream);
-    return launch_gemm<128, 256, 2, 4, 2>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, n_vis,
-                                             s_vis, s_txt, 1, nullptr, stream);
+        return launch_gemm<256, 256, 2, 4, 3>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, as, 1,
+                                                 nullptr, stream);
+    return launch_gemm<128, 256, 2, 4, 2>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, as, 1, nullptr,
+                                             stream);
+}
+
+}  // namespace
+
+extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y,
+                                int64_t ldy, int32_t *acc_out, int32_t T, int32_t N, int32_t K,
+                                int32_t n_vis, float s_vis, float s_txt, void *workspace,
+                                int64_t workspace_bytes, mquant_stream_t stream)
+{
+    const int st = check_gemm_args(xq, wp, w_scale, y, ldy, T, N, K, n_vis, s_vis, s_txt);
+    if (st != MQUANT_OK) return st;
+    if (T == 0 || N == 0) return MQUANT_OK;
+    const ActScale as = {n_vis, s_vis, s_txt, nullptr};
+    return gemm_dispatch(xq, wp, w_scale, y, ldy, acc_out, T, N, K, as, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(stream));
+}
+
+extern "C" int mquant_w4a8_gemm_rowscale(const int8_t *xq, const uint8_t *wp, const void *w_scale,
+                                         const float *row_scale, void *y, int64_t ldy,
+                                         int32_t *acc_out, int32_t T, int32_t N, int32_t K,
+                                         void *workspace, int64_t workspace_bytes,
+                                         mquant_stream_t stream)
+{
+    const int st = check_gemm_args(xq, wp, w_scale, y, ldy, T, N, K, 0, 1.0f, 1.0f);
+    if (st != MQUANT_OK) return st;
+    if (T == 0 || N == 0) return MQUANT_OK;
+    if (!row_scale) return MQUANT_ERR_NULL;
+    if (!aligned_to(row_scale, 4)) return MQUANT_ERR_ALIGNMENT;
+    const ActScale as = {0, 1.0f, 1.0f, row_scale};
+    return gemm_dispatch(xq, wp, w_scale, y, ldy, acc_out, T, N, K, as, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(stream));
 }
 
 extern "C" int64_t mquant_w4a8_linear_prefill_workspace_bytes(int32_t T, int32_t N, int32_t K)

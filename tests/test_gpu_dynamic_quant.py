@@ -1,0 +1,118 @@
+"""GPU parity of the per-token dynamic baseline (mquant_hadamard_dynquant_act,
+mquant_w4a8_gemm_rowscale) against the oracle: codes, scales and int32
+accumulators bit for bit, fp16 outputs within 1e-3 relative."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import mquant_oracle as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mq():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2502_00425_amd import binding
+    return binding
+
+
+def say(msg):
+    print(f"[parity-dyn] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_y(y_gpu, ref, what):
+    y = y_gpu.astype(np.float32)
+    tol = 1e-3 * np.maximum(np.abs(ref), 2.0 ** -14)
+    bad = np.abs(y - ref) > tol
+    assert not bad.any(), f"{what}: {int(bad.sum())} outputs beyond 1e-3 (first {np.argwhere(bad)[:3].tolist()})"
+
+
+def make_x(rng, T, K):
+    """Token magnitudes spread over three decades, a few outlier channels, one all-zero token."""
+    x = rng.standard_normal((T, K)) * rng.uniform(0.02, 20.0, size=(T, 1))
+    x[:, [3 % K, 97 % K]] *= 40.0
+    x = np.clip(x, -60000, 60000).astype(np.float16)
+    if T > 2:
+        x[T // 2] = 0
+    return x
+
+
+@pytest.mark.parametrize("T,K,B", [
+    (1, 512, 512), (5, 3584, 512), (67, 3584, 512), (33, 18944, 512), (9, 8192, 128), (7, 29568, 128),
+    (12, 2048, 1024), (6, 16384, 1024), (19, 264, 8), (4, 64, 1), (3, 32768, 512),
+])
+def test_dynquant_codes_and_scales(mq, T, K, B):
+    say(f"dynquant T={T} K={K} B={B}")
+    rng = np.random.default_rng(T * 131 + K + B)
+    x = make_x(rng, T, K)
+    want_q, want_s = orc.dyn_quantize(orc.hadamard_rotate(x, B), B)
+    xq, s = mq.hadamard_dynquant_act(dev(x), B)
+    assert (s.cpu().numpy() == want_s).all()
+    assert (xq.cpu().numpy() == want_q).all()
+
+
+def test_dynquant_with_fused_gather(mq):
+    say("dynquant gather")
+    rng = np.random.default_rng(5)
+    T, K, B = 40, 1024, 256
+    x = make_x(rng, T, K)
+    perm = rng.permutation(T).astype(np.int32)
+    want_q, want_s = orc.dyn_quantize(orc.hadamard_rotate(x[perm], B), B)
+    xq, s = mq.hadamard_dynquant_act(dev(x), B, perm_dev=dev(perm))
+    assert (s.cpu().numpy() == want_s).all() and (xq.cpu().numpy() == want_q).all()
+
+
+def test_dynquant_rejects_rows_too_long_for_registers(mq):
+    x = torch.zeros((2, 65536), dtype=torch.float16, device="cuda")
+    with pytest.raises(mq.MQuantError) as e:
+        mq.hadamard_dynquant_act(x, 512)
+    assert e.value.status == mq.ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("T,N,K,B", [(1, 200, 832, 64), (16, 200, 832, 64), (75, 300, 1024, 512),
+                                     (300, 520, 8192, 128), (260, 264, 3584, 512)])
+def test_dynamic_linear_end_to_end(mq, T, N, K, B):
+    """Rotate + per-token quantize + GEMM (GEMV, both GEMM tiles, split-K) + per-token dequant."""
+    say(f"dynamic linear T={T} N={N} K={K}")
+    rng = np.random.default_rng(T + N + K)
+    x = make_x(rng, T, K)
+    packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+    want = orc.w4a8_linear_dynamic(x, packed, w_scale, B)
+    xq, s = mq.hadamard_dynquant_act(dev(x), B)
+    acc = torch.empty((T, N), dtype=torch.int32, device="cuda")
+    wp = mq.w4_prepack(dev(packed))
+    y = mq.w4a8_gemm_rowscale(xq, wp, dev(w_scale), s, N, acc_out=acc)
+    assert (acc.cpu().numpy() == want["acc"]).all()
+    check_y(y.cpu().numpy(), want["ref"], "dynamic linear")
+    y2 = mq.w4a8_gemm_rowscale(xq, wp, dev(w_scale), s, N)          # store path without acc_out
+    check_y(y2.cpu().numpy(), want["ref"], "dynamic linear, wide store")
+
+
+def test_dynamic_linear_config1_qkv_sampled(mq):
+    """Full-size configs[1] qkv projection, the launch configuration bench.py times; outputs
+    checked on sampled rows and channels."""
+    from paper_2502_00425_amd import workloads as wl
+    say("dynamic linear c1 qkv")
+    w = wl.workload(1)
+    inp = wl.make_linear_inputs(w, "qkv")
+    x, packed, w_scale, B = inp["x"], inp["w_packed"], inp["w_scale"], inp["had_block"]
+    T, K = x.shape
+    N = packed.shape[0]
+    rng = np.random.default_rng(1)
+    rows = np.sort(rng.choice(T, size=40, replace=False))
+    cols = np.sort(rng.choice(N, size=160, replace=False))
+    want = orc.w4a8_linear_dynamic(x, packed, w_scale, B, rows=rows, cols=cols)
+    xq, s = mq.hadamard_dynquant_act(dev(x), B)
+    assert (xq.cpu().numpy() == want["xq"]).all() and (s.cpu().numpy() == want["s_rows"]).all()
+    y = mq.w4a8_gemm_rowscale(xq, mq.w4_prepack(dev(packed)), dev(w_scale), s, N)
+    check_y(y.cpu().numpy()[np.ix_(rows, cols)], want["ref"], "c1 qkv dynamic")
