@@ -13,6 +13,7 @@
  *     Outliers after Online Hadamard Transformation"
  *   - per-token dynamic quantization (baseline) ...... Sec. 2.2, appendix on
  *     quantization granularity
+ *   - Rotation Magnitude Suppression, run-time split path .. Sec. 3.2
  *   - W4A8 integer GEMM with per-channel weight scale and per-modality
  *     activation scale ................................ Sec. 4 (Table 3 text,
  *     "Speedup" paragraphs)
@@ -150,6 +151,39 @@ void orc_dequant_rows_f32(const int32_t *acc, int64_t T, int64_t N,
         for (int64_t n = 0; n < N; ++n) {
             float a = (float)acc[i * N + n];
             ref[i * N + n] = (a * s_rows[i]) * w_scale[n];
+        }
+    }
+}
+
+/*
+ * Rotation Magnitude Suppression at run time (Sec. 3.2, "Rotation Mitigation
+ * Scheme"; figure "overview of RMS"): the flagged input channels c_0..c_{S-1}
+ * have their rows zeroed in the main int4 weight, so acc holds the main GEMM
+ * only; each flagged row lives on as a separate int4 vector wsplit[j][0..N)
+ * with one scale ssplit[j] and is applied as a GEMV on the same int8 codes,
+ * its partial output added to the main path before the result is stored:
+ *   ref[i,n] = (float(acc[i,n]) s_i) w_scale[n]
+ *              + sum_j (float(xq[i,c_j] * wsplit[j][n]) s_i) ssplit[j]
+ * accumulated in fp32 in the order j = 0, 1, ..., one rounding per operation.
+ * The paper fixes neither the split row's quantization granularity nor the
+ * order of the additions; one scale per split row and this order are the
+ * reading taken here.
+ */
+void orc_dequant_rms_f32(const int32_t *acc, const int8_t *xq, int64_t T, int64_t N, int64_t K,
+                         int64_t V, float s_vis, float s_txt, const float *w_scale,
+                         const int32_t *split_idx, const int8_t *wsplit, const float *ssplit,
+                         int64_t S, float *ref)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < T; ++i) {
+        const float s = (i < V) ? s_vis : s_txt;
+        for (int64_t n = 0; n < N; ++n) {
+            float v = ((float)acc[i * N + n] * s) * w_scale[n];
+            for (int64_t j = 0; j < S; ++j) {
+                int32_t p = (int32_t)xq[i * K + split_idx[j]] * (int32_t)wsplit[j * N + n];
+                v = v + ((float)p * s) * ssplit[j];
+            }
+            ref[i * N + n] = v;
         }
     }
 }

@@ -48,6 +48,7 @@ def _lib() -> ctypes.CDLL:
         lib.orc_unpack_w4.argtypes = [p, i64, i64, p]
         lib.orc_gemm_i8_i4_i32.argtypes = [p, p, i64, i64, i64, p]
         lib.orc_dequant_f32.argtypes = [p, i64, i64, i64, f32, f32, p, p]
+        lib.orc_dequant_rms_f32.argtypes = [p, p, i64, i64, i64, i64, f32, f32, p, p, p, p, i64, p]
         lib.orc_dyn_quantize.argtypes = [p, i64, i64, ctypes.c_double, p, p]
         lib.orc_dequant_rows_f32.argtypes = [p, i64, i64, p, p, p]
         _LIB = lib
@@ -264,6 +265,93 @@ def dequant(acc: np.ndarray, V: int, s_vis: float, s_txt: float, w_scale: np.nda
     ref = np.empty((T, N), dtype=np.float32)
     _lib().orc_dequant_f32(_ptr(acc), T, N, V, np.float32(s_vis), np.float32(s_txt),
                            _ptr(ws), _ptr(ref))
+    return ref, ref.astype(np.float16)
+
+
+# ------------------------------------------------ Rotation Magnitude Suppression
+
+def rotate_weight(W: np.ndarray, B: int) -> np.ndarray:
+    """H^T W for W [K, N] (input channels down the rows) with the orthonormal
+    block-diagonal Hadamard matrix, in float64: the weight the rotated
+    activations x H meet, so that (x H)(H^T W) = x W (Sec. 3.2, computational
+    invariance; appendix on weight outliers after the online transform)."""
+    W = np.asarray(W, dtype=np.float64)
+    K, N = W.shape
+    if K % B:
+        raise ValueError("block size must divide K")
+    Hn = hadamard_matrix(B).astype(np.float64) / math.sqrt(float(B))
+    out = np.empty_like(W)
+    for b in range(K // B):
+        out[b * B:(b + 1) * B] = Hn.T @ W[b * B:(b + 1) * B]
+    return out
+
+
+def rms_flag_channels(W: np.ndarray, B: int) -> np.ndarray:
+    """Input channels of the rotated weight that carry a channel-mean outlier
+    (the condition sqrt(n) mean(w_:j) > max_i w_ij of Sec. 3.2, taken in
+    magnitude and per Hadamard block of n = B rows): the first row of block b is
+    flagged when for some output column j the block's column mean times sqrt(B)
+    exceeds the largest magnitude of that column inside the block.  Returns the
+    sorted row indices b*B of the flagged blocks."""
+    W = np.asarray(W, dtype=np.float64)
+    K, N = W.shape
+    flagged = []
+    for b in range(K // B):
+        blk = W[b * B:(b + 1) * B]
+        lhs = math.sqrt(float(B)) * np.abs(blk.mean(axis=0))
+        rhs = np.abs(blk).max(axis=0)
+        if (lhs > rhs).any():
+            flagged.append(b * B)
+    return np.asarray(flagged, dtype=np.int32)
+
+
+def quantize_weight_rows_int4(Wt: np.ndarray):
+    """Per-output-channel symmetric int4 (Eq. (2) with b = 4, z = 0, round to
+    nearest even): Wt is [N, K]; returns (codes int8 in [-8,7], scale fp16 [N]).
+    The scale max|w|/7 is rounded to fp16 first and the codes use that value."""
+    Wt = np.asarray(Wt, dtype=np.float64)
+    amax = np.abs(Wt).max(axis=1)
+    scale = np.where(amax > 0, amax / 7.0, 1.0).astype(np.float16)
+    q = np.clip(np.rint(Wt / scale.astype(np.float64)[:, None]), -8, 7).astype(np.int8)
+    return q, scale
+
+
+def rms_split_weight(W_rot: np.ndarray, flagged: np.ndarray):
+    """Offline side of RMS for one linear (Sec. 3.2 steps 1-2): the flagged rows
+    of the rotated weight [K, N] are taken out and quantized on their own (int4,
+    one scale per row), the main matrix keeps zeros there and is quantized per
+    output channel.  Returns (wq_main int8 [N,K], w_scale fp16 [N],
+    wsplit int8 [S,N], ssplit fp32 [S])."""
+    W_rot = np.asarray(W_rot, dtype=np.float64)
+    flagged = np.asarray(flagged, dtype=np.int64)
+    main = W_rot.copy()
+    main[flagged] = 0.0
+    wq_main, w_scale = quantize_weight_rows_int4(main.T)
+    rows = W_rot[flagged]
+    amax = np.abs(rows).max(axis=1) if len(flagged) else np.zeros(0)
+    ssplit = np.where(amax > 0, amax / 7.0, 1.0).astype(np.float32)
+    wsplit = np.clip(np.rint(rows / ssplit.astype(np.float64)[:, None]), -8, 7).astype(np.int8)
+    return wq_main, w_scale, wsplit.reshape(len(flagged), W_rot.shape[1]), ssplit
+
+
+def dequant_rms(acc: np.ndarray, xq: np.ndarray, V: int, s_vis: float, s_txt: float,
+                w_scale: np.ndarray, split_idx: np.ndarray, wsplit: np.ndarray, ssplit: np.ndarray):
+    """Main-path dequantisation plus the split GEMV of the flagged channels, added
+    before the store (Sec. 3.2 step 3).  (fp32 reference, fp16 output)."""
+    acc = _c(acc, np.int32)
+    xq = _c(xq, np.int8)
+    T, N = acc.shape
+    K = xq.shape[1]
+    ws = _c(np.asarray(w_scale).astype(np.float32), np.float32)
+    idx = _c(split_idx, np.int32)
+    S = idx.shape[0]
+    wsp = _c(np.asarray(wsplit).reshape(S, N), np.int8)
+    ssp = _c(ssplit, np.float32)
+    assert xq.shape[0] == T and ssp.shape == (S,)
+    assert ((idx >= 0) & (idx < K)).all()
+    ref = np.empty((T, N), dtype=np.float32)
+    _lib().orc_dequant_rms_f32(_ptr(acc), _ptr(xq), T, N, K, V, np.float32(s_vis), np.float32(s_txt),
+                               _ptr(ws), _ptr(idx), _ptr(wsp), _ptr(ssp), S, _ptr(ref))
     return ref, ref.astype(np.float16)
 
 
