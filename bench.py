@@ -45,6 +45,7 @@ def parse_args():
     ap.add_argument("--decode-layers", type=int, default=28)
     ap.add_argument("--decode-iters", type=int, default=10)
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-rms", action="store_true", help="skip the RMS split-path leg")
     ap.add_argument("--no-dynamic", action="store_true", help="skip the per-token dynamic baseline leg")
     ap.add_argument("--no-graphs", action="store_true",
                     help="time the decode loop with plain launches instead of one HIP graph")
@@ -278,6 +279,57 @@ def main():
             dyn["front_end_us_per_step"] = round(dyn_fe_ms * 1e3, 2)
             dyn["front_end_GBps"] = round((fe_bytes + 4.0 * T * len(lin)) / (dyn_fe_ms * 1e-3) / 1e9, 1)
         result["dynamic_baseline"] = dyn
+
+    # --------------------------------------- RMS split path on the down projection (context)
+    # Main GEMM plus the split GEMV of the flagged channels fused into its epilogue, for one
+    # flagged channel (the paper's 1/18944 case) and for one per Hadamard block.
+    if not args.no_rms:
+        l = lin["down"]
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(77)
+
+        def timed_launches(fn, n=20):
+            # n launches inside one HIP graph: the Python side of the split call (array
+            # marshalling) costs more than the kernels differ by
+            fn()
+            torch.cuda.synchronize()
+            run, reps = fn, n
+            if not args.no_graphs:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for _ in range(n):
+                        fn()
+                run, reps = g.replay, 1
+                run()
+                torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                run()
+            e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / n
+
+        rms = {"projection": "down 18944x3584, T=%d" % T}
+        variants = {"plain_us": lambda: mq.w4a8_gemm(
+            l["xq"], l["wp"], l["w_scale"], l["N"], V, l["s_vis"], l["s_txt"], out=l["y"],
+            workspace=l["ws"])}
+        for n_split in (1, l["K"] // B):
+            idx = np.arange(n_split, dtype=np.int32) * B
+            sw = torch.randint(-8, 8, (n_split, l["N"]), dtype=torch.int8, device="cuda", generator=gen)
+            ss = np.linspace(0.05, 0.35, n_split, dtype=np.float32)
+            variants["split_%d_us" % n_split] = (lambda idx=idx, sw=sw, ss=ss: mq.w4a8_gemm_rms(
+                l["xq"], l["wp"], l["w_scale"], l["N"], V, l["s_vis"], l["s_txt"], idx, sw, ss,
+                out=l["y"], workspace=l["ws"]))
+        # alternate the variants and keep the best of three rounds each (clock drift between
+        # separately timed blocks is of the order of the differences)
+        best = {k: float("inf") for k in variants}
+        for _ in range(3):
+            for k, fn in variants.items():
+                best[k] = min(best[k], timed_launches(fn))
+        rms.update({k: round(v, 2) for k, v in best.items()})
+        result["rms_split"] = rms
 
     # ------------------------------------------------------------------ decode
     if not args.no_decode:

@@ -228,6 +228,33 @@ int mquant_w4a8_gemm_rowscale(const int8_t *xq_dev, const uint8_t *w_prepacked_d
                               void *workspace_dev, int64_t workspace_bytes,
                               mquant_stream_t stream);
 
+/*
+ * DEVICE.  The GEMM / GEMV for a linear marked by Rotation Magnitude
+ * Suppression (Sec. 3.2: split the flagged channels into a separate GEMV, zero
+ * their rows in the main weight, add the partial output back; the RMS
+ * algorithm of the appendix marks the layers offline).  The main weight
+ * w_prepacked_dev holds zeros in the n_split flagged input channels; every
+ * flagged channel c_j comes with its own int4 row and scale:
+ *   y[i, n] = fp16( (float(acc[i, n]) * s_i) * float(w_scale[n])
+ *                   + sum_j (float(xq[i, c_j] * split_w[j, n]) * s_i) * split_scale[j] )
+ * in fp32, terms added in the order j = 0, 1, ...
+ *   split_idx_host   : HOST int32 [n_split], channel indices in [0, K) (per-layer
+ *                      constants; they travel as kernel arguments)
+ *   split_w_dev      : DEVICE int8 [n_split, N], int4 values in [-8, 7], one per byte
+ *   split_scale_host : HOST fp32 [n_split], finite
+ *   n_split          : 0 .. 64; 0 makes the call identical to mquant_w4a8_gemm.
+ *                      The epilogue costs O(n_split) per output.
+ *   acc_out_dev      : receives the main-path accumulators only
+ * Other arguments, workspace and errors as in mquant_w4a8_gemm; ERR_BAD_SHAPE
+ * for n_split or an index outside its range or a non-finite scale.
+ */
+int mquant_w4a8_gemm_rms(const int8_t *xq_dev, const uint8_t *w_prepacked_dev,
+                         const void *w_scale_dev, void *y_dev, int64_t ldy, int32_t *acc_out_dev,
+                         int32_t T, int32_t N, int32_t K, int32_t n_vis, float s_vis, float s_txt,
+                         const int32_t *split_idx_host, const int8_t *split_w_dev,
+                         const float *split_scale_host, int32_t n_split,
+                         void *workspace_dev, int64_t workspace_bytes, mquant_stream_t stream);
+
 /* Workspace of the fused prefill entry: the int8 activations plus whatever
  * mquant_w4a8_gemm needs. */
 int64_t mquant_w4a8_linear_prefill_workspace_bytes(int32_t T, int32_t N, int32_t K);

@@ -27,7 +27,7 @@ EXPORTS = (
     "mquant_aifs_remap_mask", "mquant_hadamard_quant_act", "mquant_hadamard_absmax",
     "mquant_w4_prepacked_bytes", "mquant_w4_prepack", "mquant_w4a8_workspace_bytes",
     "mquant_w4a8_gemm", "mquant_w4a8_linear_prefill_workspace_bytes", "mquant_w4a8_linear_prefill",
-    "mquant_hadamard_dynquant_act", "mquant_w4a8_gemm_rowscale",
+    "mquant_hadamard_dynquant_act", "mquant_w4a8_gemm_rowscale", "mquant_w4a8_gemm_rms",
 )
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGNMENT = 0, -1, -2, -3, -4, -5, -6
@@ -60,6 +60,8 @@ def _load() -> ctypes.CDLL:
     lib.mquant_hadamard_absmax.argtypes = [p, i64, i32, i32, i32, p, p]
     lib.mquant_hadamard_dynquant_act.argtypes = [p, i64, p, p, p, i32, i32, i32, p]
     lib.mquant_w4a8_gemm_rowscale.argtypes = [p, p, p, p, p, i64, p, i32, i32, i32, p, i64, p]
+    lib.mquant_w4a8_gemm_rms.argtypes = [p, p, p, p, i64, p, i32, i32, i32, i32, f32, f32, p, p, p, i32,
+                                         p, i64, p]
     lib.mquant_w4_prepacked_bytes.restype = i64
     lib.mquant_w4_prepacked_bytes.argtypes = [i32, i32]
     lib.mquant_w4_prepack.argtypes = [p, p, i32, i32, p]
@@ -233,6 +235,33 @@ def w4a8_gemm_rowscale(xq, w_prepacked, w_scale, row_scale, N: int, out=None, ac
                                          _dp(out), out.stride(0), _dp(acc_out), T, N, K,
                                          _dp(workspace), ws_bytes, _stream()),
            "mquant_w4a8_gemm_rowscale")
+    return out
+
+
+def w4a8_gemm_rms(xq, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float, s_txt: float,
+                  split_idx, split_w, split_scale, out=None, acc_out=None, workspace=None):
+    """split_idx (int32) and split_scale (fp32) are HOST arrays (per-layer constants),
+    split_w is a device tensor int8 [n_split, N]."""
+    import torch
+    T, K = xq.shape
+    if split_idx is None:
+        n_split, idx_p, sc_p = 0, None, None
+    else:
+        idx = np.ascontiguousarray(split_idx, dtype=np.int32)
+        sc = np.ascontiguousarray(split_scale, dtype=np.float32)
+        n_split = int(idx.shape[0])
+        idx_p, sc_p = idx.ctypes.data_as(ctypes.c_void_p), sc.ctypes.data_as(ctypes.c_void_p)
+    if out is None:
+        out = torch.empty((T, N), dtype=torch.float16, device=xq.device)
+    if workspace is None:
+        need = w4a8_workspace_bytes(T, N, K)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=xq.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.mquant_w4a8_gemm_rms(_dp(xq), _dp(w_prepacked), _dp(w_scale), _dp(out), out.stride(0),
+                                    _dp(acc_out), T, N, K, n_vis, s_vis, s_txt, idx_p,
+                                    _dp(split_w), sc_p, n_split, _dp(workspace),
+                                    ws_bytes, _stream()), "mquant_w4a8_gemm_rms")
     return out
 
 

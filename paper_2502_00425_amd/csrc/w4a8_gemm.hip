@@ -94,25 +94,65 @@ __device__ __forceinline__ v4i as_v4i(const uint4 u)
 // Row of the 32x32 MFMA result held in accumulator register r by k-group g.
 __device__ __forceinline__ int acc_row(int r, int g) { return (r >> 2) * 8 + g * 4 + (r & 3); }
 
-// Activation scale of a row: the two static modality scales split at row n_vis
-// (Eq. (3)), or, for the per-token dynamic baseline, one scale per row.
-struct ActScale {
+// Everything the dequantising epilogue needs besides the accumulator and the
+// per-channel weight scale.  Activation scale of a row: the two static modality
+// scales split at row n_vis (Eq. (3)), or, for the per-token dynamic baseline,
+// one scale per row.  Rotation Magnitude Suppression (Sec. 3.2): n_split flagged
+// input channels were zeroed in the main weight; each lives on as an int4 row
+// split_w[j][0..N) (one byte per value) with one scale, and its product with the
+// token's int8 code of that channel is added to the main path before the store.
+constexpr int kEpiStatic = 0, kEpiRowScale = 1, kEpiSplit = 2;
+constexpr int kMaxSplitChannels = 64;     // flagged channels per linear
+
+struct Epilogue {
     int32_t n_vis;
     float s_vis, s_txt;
     const float *rows;          // nullptr: static scales
-    __device__ __forceinline__ float of(int32_t row) const
+    int32_t n_split;            // 0: no split path
+    int32_t K;
+    const int8_t *xq;
+    const int8_t *split_w;
+    // Per-layer constants, passed by value so that a kernel reads them as scalars
+    // instead of chasing two more pointers per output.
+    int32_t split_idx[kMaxSplitChannels];
+    float split_scale[kMaxSplitChannels];
+
+    // EPI selects the code compiled into a kernel: the static path must not pay for
+    // the pointer test and the split loop (measured: 10 % of the 1280 x 3584 x 37888 GEMM).
+    template <int EPI>
+    __device__ __forceinline__ float scale_of(int32_t row) const
     {
-        return rows != nullptr ? rows[row] : (row < n_vis ? s_vis : s_txt);
+        if constexpr (EPI == kEpiRowScale) return rows[row];
+        else return row < n_vis ? s_vis : s_txt;
+    }
+    // (float(acc) * s_row) * ws, plus the split terms in the order j = 0, 1, ...;
+    // one rounding per operation.  row < T and n < N.
+    template <int EPI>
+    __device__ __forceinline__ float dequant(int32_t acc, float s_row, int32_t row, int32_t n,
+                                             int32_t N, float ws) const
+    {
+        float v = (static_cast<float>(acc) * s_row) * ws;
+        if constexpr (EPI == kEpiSplit) {
+            for (int32_t j = 0; j < n_split; ++j) {
+                const int32_t c = split_idx[j];           // validated on the host
+                const int32_t p = static_cast<int32_t>(xq[static_cast<int64_t>(row) * K + c]) *
+                                  static_cast<int32_t>(split_w[static_cast<int64_t>(j) * N + n]);
+                v = v + (static_cast<float>(p) * s_row) * split_scale[j];
+            }
+        }
+        return v;
     }
 };
 
-__device__ __forceinline__ void store_out(int32_t acc16, int32_t row, int32_t n, float s_row,
+template <int EPI>
+__device__ __forceinline__ void store_out(int32_t acc16, int32_t row, int32_t n, const Epilogue &ep,
                                           float ws, __half *y, int64_t ldy, int32_t *acc_out,
                                           int32_t N)
 {
     const int32_t acc = acc16 >> 4;                       // exact: acc16 = 16 * acc
-    const float v = (static_cast<float>(acc) * s_row) * ws;
-    y[static_cast<int64_t>(row) * ldy + n] = __float2half_rn(v);
+    const float s_row = ep.scale_of<EPI>(row);
+    y[static_cast<int64_t>(row) * ldy + n] =
+        __float2half_rn(ep.dequant<EPI>(acc, s_row, row, n, N, ws));
     if (acc_out) acc_out[static_cast<int64_t>(row) * N + n] = acc;
 }
 
@@ -189,11 +229,11 @@ __device__ __forceinline__ void tile_of_group(int32_t id, int32_t tiles_m, int32
     tn = in_band / rows;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES>
+template <int BM, int BN, int WM, int WN, int STAGES, int EPI>
 __global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_kernel(
     const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
     __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
-    int32_t K, ActScale as, int32_t tiles_m, int32_t tiles_n,
+    int32_t K, Epilogue ep, int32_t tiles_m, int32_t tiles_n,
     int32_t n_tiles32, int32_t splits, int32_t kb_per_split, int32_t *__restrict__ partial,
     int32_t wide_store, int32_t band)
 {
@@ -435,10 +475,7 @@ __global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_ke
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int32_t row = wave_row0 + mt * 32 + acc_row(r, g);
-                    if (row < T) {
-                        const float s_row = as.of(row);
-                        store_out(acc[mt][nt][r], row, n, s_row, ws, y, ldy, acc_out, N);
-                    }
+                    if (row < T) store_out<EPI>(acc[mt][nt][r], row, n, ep, ws, y, ldy, acc_out, N);
                 }
             }
         }
@@ -467,11 +504,14 @@ __global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_ke
         for (int r = 0; r < 16; ++r) {
             const int rl = acc_row(r, g);
             const int32_t row = wave_row0 + mt * 32 + rl;
-            const float s_row = as.of(row);
+            const int32_t row_in = row < T ? row : T - 1;          // rows past T are never stored
+            const float s_row = ep.scale_of<EPI>(row_in);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 const int32_t a = acc[mt][nt][r] >> 4;             // exact: the sum holds 16 * acc
-                const float v = (static_cast<float>(a) * s_row) * ws[nt];
+                int32_t n = wave_n0 + nt * 32 + l32;
+                n = n < N ? n : N - 1;                             // only read by the split path
+                const float v = ep.dequant<EPI>(a, s_row, row_in, n, N, ws[nt]);
                 *reinterpret_cast<__half *>(patch + rl * ROWB + (nt * 32 + l32) * 2) =
                     __float2half_rn(v);
             }
@@ -491,10 +531,11 @@ __global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_ke
 
 // Sums the split-K partials (int32, x16) and applies the dequant epilogue.
 // Four consecutive channels per thread; N % 4 == 0.
+template <int EPI>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(
     const int32_t *__restrict__ partial, int32_t splits, int32_t T, int32_t N,
     const __half *__restrict__ w_scale, __half *__restrict__ y, int64_t ldy,
-    int32_t *__restrict__ acc_out, ActScale as)
+    int32_t *__restrict__ acc_out, Epilogue ep)
 {
     const int64_t quads = static_cast<int64_t>(T) * (N / 4);
     const int64_t plane = static_cast<int64_t>(T) * N;
@@ -511,12 +552,30 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(
             sum.z += p.z;
             sum.w += p.w;
         }
-        const float s_row = as.of(row);
         const int32_t a[4] = {sum.x >> 4, sum.y >> 4, sum.z >> 4, sum.w >> 4};
+        const float s_row = ep.scale_of<EPI>(row);
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            v[e] = (static_cast<float>(a[e]) * s_row) * __half2float(w_scale[n + e]);
+        if constexpr (EPI == kEpiSplit) {
+            // same terms and order as Epilogue::dequant, with the token's code read once per
+            // flagged channel and the four weights of the quad in one 4-byte load
+            for (int32_t j = 0; j < ep.n_split; ++j) {
+                const int32_t code = ep.xq[static_cast<int64_t>(row) * ep.K + ep.split_idx[j]];
+                const uint32_t w4 = *reinterpret_cast<const uint32_t *>(
+                    ep.split_w + static_cast<int64_t>(j) * N + n);
+                const float sc = ep.split_scale[j];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int32_t w = static_cast<int8_t>(w4 >> (8 * e));
+                    v[e] = v[e] + (static_cast<float>(code * w) * s_row) * sc;
+                }
+            }
+        }
         __half h[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            h[j] = __float2half_rn((static_cast<float>(a[j]) * s_row) * __half2float(w_scale[n + j]));
+        for (int e = 0; e < 4; ++e) h[e] = __float2half_rn(v[e]);
         __half *dst = y + static_cast<int64_t>(row) * ldy + n;
         if ((reinterpret_cast<uintptr_t>(dst) & 7) == 0) {
             *reinterpret_cast<uint2 *>(dst) = *reinterpret_cast<const uint2 *>(h);
@@ -538,11 +597,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(
 // free: addresses past a wave's K range are clamped and the weights masked to
 // zero, and lanes whose token row is >= T read row T-1 (rows >= T of the MFMA
 // result are never stored).  The partial sums of the waves meet in LDS.
-template <int NWAVES, int KT>
+template <int NWAVES, int KT, int EPI>
 __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
     const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
     __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
-    int32_t K, ActScale as)
+    int32_t K, Epilogue ep)
 {
     typedef unsigned int v4u __attribute__((ext_vector_type(4)));
     __shared__ int32_t red[NWAVES][16][64];
@@ -621,8 +680,7 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
             int32_t sum = 0;
 #pragma unroll
             for (int w = 0; w < NWAVES; ++w) sum += red[w][r][lane];
-            const float s_row = as.of(row);
-            store_out(sum, row, n, s_row, ws, y, ldy, acc_out, N);
+            store_out<EPI>(sum, row, n, ep, ws, y, ldy, acc_out, N);
         }
     }
 }
@@ -666,9 +724,9 @@ int plan_splits(int32_t T, int32_t N, int32_t K)
     return static_cast<int>(s);
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES>
+template <int BM, int BN, int WM, int WN, int STAGES, int EPI>
 int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y, int64_t ldy,
-                int32_t *acc_out, int32_t T, int32_t N, int32_t K, ActScale as, int32_t splits,
+                int32_t *acc_out, int32_t T, int32_t N, int32_t K, Epilogue ep, int32_t splits,
                 int32_t *partial, hipStream_t stream)
 {
     const int32_t tiles_m = static_cast<int32_t>(ceil_div(T, BM));
@@ -678,7 +736,7 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
     const size_t lds = static_cast<size_t>(STAGES) * (BM * 128 + BN * 64);
     const int32_t wide_store =
         (N % 8 == 0 && ldy % 8 == 0 && aligned_to(y, 16) && acc_out == nullptr) ? 1 : 0;
-    auto kern = w4a8_gemm_kernel<BM, BN, WM, WN, STAGES>;
+    auto kern = w4a8_gemm_kernel<BM, BN, WM, WN, STAGES, EPI>;
     // Band height of the tile order: all tile-rows when there are few (every B panel is then
     // read by one XCD only), else equal bands of about six rows.
     const int32_t band = tiles_m <= 8 ? tiles_m
@@ -693,16 +751,16 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
     }
     MQ_LAUNCH(kern, dim3(tiles_m * tiles_n * splits), dim3(WM * WN * 64), lds, stream, xq,
                        reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
-                       static_cast<__half *>(y), ldy, acc_out, T, N, K, as, tiles_m, tiles_n, n_tiles32, splits, kb_per_split,
+                       static_cast<__half *>(y), ldy, acc_out, T, N, K, ep, tiles_m, tiles_n, n_tiles32, splits, kb_per_split,
                        splits > 1 ? partial : nullptr, wide_store, band);
     int st = launch_status();
     if (st != MQUANT_OK || splits == 1) return st;
     const int64_t quads = static_cast<int64_t>(T) * (N / 4);
     int64_t blocks = ceil_div(quads, 256);
     if (blocks > 8 * kNumCU) blocks = 8 * kNumCU;
-    MQ_LAUNCH(splitk_reduce_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
+    MQ_LAUNCH(splitk_reduce_kernel<EPI>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
                        stream, partial, splits, T, N, static_cast<const __half *>(w_scale),
-                       static_cast<__half *>(y), ldy, acc_out, as);
+                       static_cast<__half *>(y), ldy, acc_out, ep);
     return launch_status();
 }
 
@@ -759,10 +817,11 @@ extern "C" int64_t mquant_w4a8_workspace_bytes(int32_t T, int32_t N, int32_t K)
 
 namespace {
 
-// Shared body of the two GEMM entry points; `as` carries either the static or
-// the per-row activation scales.  Arguments are validated by the callers.
+// Shared body of the GEMM entry points; `ep` carries the activation scales (static or
+// per row) and the optional split channels.  Arguments are validated by the callers.
+template <int EPI>
 int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *y, int64_t ldy,
-                  int32_t *acc_out, int32_t T, int32_t N, int32_t K, ActScale as, void *workspace,
+                  int32_t *acc_out, int32_t T, int32_t N, int32_t K, Epilogue ep, void *workspace,
                   int64_t workspace_bytes, hipStream_t stream)
 {
     if (T <= kGemvMaxT || K % 128 != 0) {
@@ -770,21 +829,22 @@ int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void
         // (only reached for K % 128 != 0, which the prefill kernel does not take).
         for (int32_t t0 = 0; t0 < T; t0 += kGemvMaxT) {
             const int32_t tt = T - t0 < kGemvMaxT ? T - t0 : kGemvMaxT;
-            ActScale slab = as;
-            int32_t nv = as.n_vis - t0;
+            Epilogue slab = ep;
+            int32_t nv = ep.n_vis - t0;
             slab.n_vis = nv < 0 ? 0 : (nv > tt ? tt : nv);
-            if (as.rows != nullptr) slab.rows = as.rows + t0;
+            if (ep.rows != nullptr) slab.rows = ep.rows + t0;
+            slab.xq = xq + static_cast<int64_t>(t0) * K;
             const unsigned n_tiles = static_cast<unsigned>(ceil_div(N, 32));
             const int8_t *xs = xq + static_cast<int64_t>(t0) * K;
             __half *ys = static_cast<__half *>(y) + static_cast<int64_t>(t0) * ldy;
             int32_t *accs = acc_out ? acc_out + static_cast<int64_t>(t0) * N : nullptr;
             // Few n-tiles: more waves per tile to keep enough loads in flight.
             if (n_tiles >= 256)
-                MQ_LAUNCH((w4a8_gemv_kernel<8, 4>), dim3(n_tiles), dim3(512), 0, stream, xs,
+                MQ_LAUNCH((w4a8_gemv_kernel<8, 4, EPI>), dim3(n_tiles), dim3(512), 0, stream, xs,
                           reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
                           ys, ldy, accs, tt, N, K, slab);
             else
-                MQ_LAUNCH((w4a8_gemv_kernel<16, 4>), dim3(n_tiles), dim3(1024), 0, stream, xs,
+                MQ_LAUNCH((w4a8_gemv_kernel<16, 4, EPI>), dim3(n_tiles), dim3(1024), 0, stream, xs,
                           reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
                           ys, ldy, accs, tt, N, K, slab);
             const int ls = launch_status();
@@ -800,13 +860,13 @@ int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void
         const int64_t need = static_cast<int64_t>(splits) * T * N * 4;
         if (!workspace || workspace_bytes < need) return MQUANT_ERR_WORKSPACE;
         if (!aligned_to(workspace, 256)) return MQUANT_ERR_ALIGNMENT;
-        return launch_gemm<256, 256, 2, 4, 3>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, as, splits,
+        return launch_gemm<256, 256, 2, 4, 3, EPI>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, ep, splits,
                                                  static_cast<int32_t *>(workspace), stream);
     }
     if ((force_tile < 0 ? pick_gemm_tile(T, N) : force_tile) == 0)
-        return launch_gemm<256, 256, 2, 4, 3>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, as, 1,
+        return launch_gemm<256, 256, 2, 4, 3, EPI>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, ep, 1,
                                                  nullptr, stream);
-    return launch_gemm<128, 256, 2, 4, 2>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, as, 1, nullptr,
+    return launch_gemm<128, 256, 2, 4, 2, EPI>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, ep, 1, nullptr,
                                              stream);
 }
 
@@ -820,8 +880,9 @@ extern "C" int mquant_w4a8_gemm(const int8_t *xq, const uint8_t *wp, const void 
     const int st = check_gemm_args(xq, wp, w_scale, y, ldy, T, N, K, n_vis, s_vis, s_txt);
     if (st != MQUANT_OK) return st;
     if (T == 0 || N == 0) return MQUANT_OK;
-    const ActScale as = {n_vis, s_vis, s_txt, nullptr};
-    return gemm_dispatch(xq, wp, w_scale, y, ldy, acc_out, T, N, K, as, workspace, workspace_bytes,
+    Epilogue ep = {};
+    ep.n_vis = n_vis, ep.s_vis = s_vis, ep.s_txt = s_txt, ep.K = K, ep.xq = xq;
+    return gemm_dispatch<kEpiStatic>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, ep, workspace, workspace_bytes,
                          static_cast<hipStream_t>(stream));
 }
 
@@ -836,9 +897,42 @@ extern "C" int mquant_w4a8_gemm_rowscale(const int8_t *xq, const uint8_t *wp, co
     if (T == 0 || N == 0) return MQUANT_OK;
     if (!row_scale) return MQUANT_ERR_NULL;
     if (!aligned_to(row_scale, 4)) return MQUANT_ERR_ALIGNMENT;
-    const ActScale as = {0, 1.0f, 1.0f, row_scale};
-    return gemm_dispatch(xq, wp, w_scale, y, ldy, acc_out, T, N, K, as, workspace, workspace_bytes,
+    Epilogue ep = {};
+    ep.s_vis = 1.0f, ep.s_txt = 1.0f, ep.rows = row_scale, ep.K = K, ep.xq = xq;
+    return gemm_dispatch<kEpiRowScale>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, ep, workspace, workspace_bytes,
                          static_cast<hipStream_t>(stream));
+}
+
+extern "C" int mquant_w4a8_gemm_rms(const int8_t *xq, const uint8_t *wp, const void *w_scale,
+                                    void *y, int64_t ldy, int32_t *acc_out, int32_t T, int32_t N,
+                                    int32_t K, int32_t n_vis, float s_vis, float s_txt,
+                                    const int32_t *split_idx, const int8_t *split_w,
+                                    const float *split_scale, int32_t n_split, void *workspace,
+                                    int64_t workspace_bytes, mquant_stream_t stream)
+{
+    const int st = check_gemm_args(xq, wp, w_scale, y, ldy, T, N, K, n_vis, s_vis, s_txt);
+    if (st != MQUANT_OK) return st;
+    if (n_split < 0 || n_split > kMaxSplitChannels) return MQUANT_ERR_BAD_SHAPE;
+    if (T == 0 || N == 0) return MQUANT_OK;
+    Epilogue ep = {};
+    ep.n_vis = n_vis, ep.s_vis = s_vis, ep.s_txt = s_txt, ep.K = K, ep.xq = xq;
+    if (n_split > 0) {
+        if (!split_idx || !split_w || !split_scale) return MQUANT_ERR_NULL;
+        if (!aligned_to(split_w, 4)) return MQUANT_ERR_ALIGNMENT;
+        for (int32_t j = 0; j < n_split; ++j) {
+            if (split_idx[j] < 0 || split_idx[j] >= K) return MQUANT_ERR_BAD_SHAPE;
+            if (!isfinite(split_scale[j])) return MQUANT_ERR_BAD_SHAPE;
+            ep.split_idx[j] = split_idx[j];
+            ep.split_scale[j] = split_scale[j];
+        }
+        ep.n_split = n_split;
+        ep.split_w = split_w;
+    }
+    if (n_split == 0)
+        return gemm_dispatch<kEpiStatic>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, ep, workspace,
+                                         workspace_bytes, static_cast<hipStream_t>(stream));
+    return gemm_dispatch<kEpiSplit>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, ep, workspace,
+                                    workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int64_t mquant_w4a8_linear_prefill_workspace_bytes(int32_t T, int32_t N, int32_t K)
