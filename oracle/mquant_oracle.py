@@ -156,6 +156,58 @@ def causal_attention_f64(Q, K, Vv, mask) -> np.ndarray:
     return a @ Vv
 
 
+def aifs_attention_f64(q, k, v, pos, n_q_heads: int, n_kv_heads: int, rows=None) -> np.ndarray:
+    """Multi-head causal attention on AIFS-ordered tokens (Sec. 3.1, Eq. (5)-(6)).
+
+    q is [T, n_q_heads*D], k and v are [T, n_kv_heads*D] (token-major, heads side
+    by side; query head h reads key/value head h // (n_q_heads // n_kv_heads)),
+    pos[i] is the position token i had in the original sequence (the AIFS index
+    vector).  Token i attends token j exactly when pos[j] <= pos[i]: the unified
+    mask M^u[i,j] = M[pos[i], pos[j]] of the causal M, which for one visual segment
+    is the three-region rule of Eq. (6).  softmax(q k^T / sqrt(D) + M^u) v per head,
+    everything in fp64.  `rows` restricts the queries (for spot checks)."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    pos = np.asarray(pos, dtype=np.int64)
+    T = q.shape[0]
+    D = q.shape[1] // n_q_heads
+    assert k.shape == (T, n_kv_heads * D) and v.shape == k.shape and n_q_heads % n_kv_heads == 0
+    sel = np.arange(T) if rows is None else np.asarray(rows, dtype=np.int64)
+    allowed = pos[None, :] <= pos[sel][:, None]
+    out = np.empty((len(sel), n_q_heads * D), dtype=np.float64)
+    group = n_q_heads // n_kv_heads
+    for h in range(n_q_heads):
+        g = h // group
+        out[:, h * D:(h + 1) * D] = causal_attention_f64(
+            q[sel, h * D:(h + 1) * D], k[:, g * D:(g + 1) * D], v[:, g * D:(g + 1) * D], allowed)
+    return out
+
+
+def rope_inv_freq(D: int, base: float = 10000.0) -> np.ndarray:
+    """theta_i = base^(-2(i-1)/D), i = 1..D/2 (appendix "Rotary Position Embedding for AIFS")."""
+    return np.asarray([base ** (-2.0 * i / D) for i in range(D // 2)], dtype=np.float64)
+
+
+def rope_apply_f64(x, pos, n_heads: int, base: float = 10000.0) -> np.ndarray:
+    """Rotary position embedding with the reordered position ids (appendix "Rotary
+    Position Embedding for AIFS"): for token i at original position p = pos[i],
+    every head's channel pair (2j, 2j+1) is rotated by the angle p * theta_j,
+        x'[2j]   = x[2j] cos - x[2j+1] sin,   x'[2j+1] = x[2j] sin + x[2j+1] cos
+    (the block-diagonal rotation matrix printed there).  x is [T, n_heads*D]; fp64."""
+    x = np.asarray(x, dtype=np.float64)
+    pos = np.asarray(pos, dtype=np.float64)
+    T = x.shape[0]
+    D = x.shape[1] // n_heads
+    ang = pos[:, None] * rope_inv_freq(D, base)[None, :]          # [T, D/2]
+    c, s_ = np.cos(ang), np.sin(ang)
+    xr = x.reshape(T, n_heads, D // 2, 2)
+    out = np.empty_like(xr)
+    out[..., 0] = xr[..., 0] * c[:, None, :] - xr[..., 1] * s_[:, None, :]
+    out[..., 1] = xr[..., 0] * s_[:, None, :] + xr[..., 1] * c[:, None, :]
+    return out.reshape(T, n_heads * D)
+
+
 # --------------------------------------------------------------------------
 # Online Hadamard rotation (Sec. 3.2; appendix on the Walsh-Hadamard matrix)
 # --------------------------------------------------------------------------
