@@ -274,6 +274,52 @@ int mquant_w4a8_linear_prefill(const void *x_dev, int64_t ldx, const int32_t *pe
                                void *workspace_dev, int64_t workspace_bytes,
                                mquant_stream_t stream);
 
+/* -------------------------------------------------------------------------
+ * Attention on AIFS-ordered tokens (Sec. 3.1, Eq. (5)-(6)) and rotary position
+ * embedding with the reordered position ids (appendix "Rotary Position
+ * Embedding for AIFS").  fp16 tensors, token-major, heads side by side:
+ * q, o [T, n_q_heads * head_dim], k, v [T, n_kv_heads * head_dim]; query head h
+ * uses key/value head h / (n_q_heads / n_kv_heads).  head_dim must be 128.
+ * ---------------------------------------------------------------------- */
+
+/*
+ * DEVICE, in place.  Rotates every head's channel pairs (2j, 2j+1) of token i by
+ * the angle pos[i] * base^(-2j/head_dim): the rotary embedding with the token's
+ * ORIGINAL position as its id, so that reordered tokens keep their embedding.
+ *   x_dev   : fp16 [T, ldx], the first n_heads * head_dim channels of a row are rotated
+ *   pos_dev : int32 [T], original position of AIFS row i (the AIFS index vector)
+ *   base    : > 1 (10000 in the paper)
+ * Errors: ERR_NULL, ERR_BAD_SHAPE, ERR_UNSUPPORTED (head_dim != 128), ERR_ALIGNMENT
+ *         (ldx odd, x not 4-byte aligned).
+ */
+int mquant_rope_apply(void *x_dev, int64_t ldx, const int32_t *pos_dev, int32_t T,
+                      int32_t n_heads, int32_t head_dim, double base, mquant_stream_t stream);
+
+/* Workspace of mquant_aifs_attention: the transposed values and two ints per key tile. */
+int64_t mquant_aifs_attention_workspace_bytes(int32_t T, int32_t n_kv_heads, int32_t head_dim);
+
+/*
+ * DEVICE.  o = softmax(q k^T / sqrt(head_dim) + M^u) v per head, where token i
+ * may attend token j exactly when pos[j] <= pos[i]: the unified causal mask
+ * M^u[i,j] = M[pos[i], pos[j]] (Eq. (5) -> Eq. (6); for one visual segment the
+ * three-region rule printed there), evaluated from the positions per tile; no
+ * [T, T] mask is read or written.  fp32 softmax statistics, fp16 MFMA operands.
+ *   q_dev, k_dev, v_dev, o_dev : as above, leading dimensions in elements
+ *                                (ldq, ldk multiples of 8, ldo of 4; q, k 16-byte
+ *                                aligned, o 8-byte); o is written
+ *   pos_dev       : int32 [T]; any values (ties attend each other)
+ *   workspace_dev : mquant_aifs_attention_workspace_bytes(...) bytes, 256-byte
+ *                   aligned; scratch, concurrent calls must not share it
+ * Errors: ERR_NULL, ERR_BAD_SHAPE (n_q_heads not a multiple of n_kv_heads, a
+ *         leading dimension too small), ERR_UNSUPPORTED (head_dim != 128),
+ *         ERR_WORKSPACE, ERR_ALIGNMENT.
+ */
+int mquant_aifs_attention(const void *q_dev, int64_t ldq, const void *k_dev, int64_t ldk,
+                          const void *v_dev, int64_t ldv, void *o_dev, int64_t ldo,
+                          const int32_t *pos_dev, int32_t T, int32_t n_q_heads, int32_t n_kv_heads,
+                          int32_t head_dim, void *workspace_dev, int64_t workspace_bytes,
+                          mquant_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,6 +28,7 @@ EXPORTS = (
     "mquant_w4_prepacked_bytes", "mquant_w4_prepack", "mquant_w4a8_workspace_bytes",
     "mquant_w4a8_gemm", "mquant_w4a8_linear_prefill_workspace_bytes", "mquant_w4a8_linear_prefill",
     "mquant_hadamard_dynquant_act", "mquant_w4a8_gemm_rowscale", "mquant_w4a8_gemm_rms",
+    "mquant_rope_apply", "mquant_aifs_attention_workspace_bytes", "mquant_aifs_attention",
 )
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGNMENT = 0, -1, -2, -3, -4, -5, -6
@@ -72,8 +73,12 @@ def _load() -> ctypes.CDLL:
     lib.mquant_w4a8_linear_prefill_workspace_bytes.argtypes = [i32, i32, i32]
     lib.mquant_w4a8_linear_prefill.argtypes = [p, i64, p, p, p, p, i64, i32, i32, i32, i32, f32, f32,
                                                i32, p, i64, p]
+    lib.mquant_rope_apply.argtypes = [p, i64, p, i32, i32, i32, ctypes.c_double, p]
+    lib.mquant_aifs_attention_workspace_bytes.restype = i64
+    lib.mquant_aifs_attention_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.mquant_aifs_attention.argtypes = [p, i64, p, i64, p, i64, p, i64, p, i32, i32, i32, i32, p, i64, p]
     for name in EXPORTS:
-        if name not in ("mquant_status_string", "mquant_w4_prepacked_bytes",
+        if name not in ("mquant_status_string", "mquant_w4_prepacked_bytes", "mquant_aifs_attention_workspace_bytes",
                         "mquant_w4a8_workspace_bytes", "mquant_w4a8_linear_prefill_workspace_bytes",
                         "mquant_version"):
             getattr(lib, name).restype = ctypes.c_int
@@ -283,4 +288,37 @@ def w4a8_linear_prefill(x, perm_dev, w_prepacked, w_scale, N: int, n_vis: int, s
                                           _dp(w_scale), _dp(out), out.stride(0), T, N, K, n_vis,
                                           s_vis, s_txt, had_block, _dp(workspace), ws_bytes,
                                           _stream()), "mquant_w4a8_linear_prefill")
+    return out
+
+
+def rope_apply(x, pos_dev, n_heads: int, head_dim: int = 128, base: float = 10000.0):
+    """In place on x [T, >= n_heads*head_dim] fp16."""
+    T = x.shape[0]
+    _check(lib.mquant_rope_apply(_dp(x), x.stride(0), _dp(pos_dev), T, n_heads, head_dim,
+                                 float(base), _stream()), "mquant_rope_apply")
+    return x
+
+
+def aifs_attention_workspace_bytes(T: int, n_kv_heads: int, head_dim: int = 128) -> int:
+    n = int(lib.mquant_aifs_attention_workspace_bytes(T, n_kv_heads, head_dim))
+    if n < 0:
+        raise MQuantError(n, "mquant_aifs_attention_workspace_bytes")
+    return n
+
+
+def aifs_attention(q, k, v, pos_dev, n_q_heads: int, n_kv_heads: int, head_dim: int = 128,
+                   out=None, workspace=None):
+    """q [T, >= Hq*D], k, v [T, >= Hkv*D] fp16 views (row strides are passed on)."""
+    import torch
+    T = q.shape[0]
+    if out is None:
+        out = torch.empty((T, n_q_heads * head_dim), dtype=torch.float16, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(max(aifs_attention_workspace_bytes(T, n_kv_heads, head_dim), 256),
+                                dtype=torch.uint8, device=q.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib.mquant_aifs_attention(_dp(q), q.stride(0), _dp(k), k.stride(0), _dp(v), v.stride(0),
+                                     _dp(out), out.stride(0), _dp(pos_dev), T, n_q_heads, n_kv_heads,
+                                     head_dim, _dp(workspace), ws_bytes, _stream()),
+           "mquant_aifs_attention")
     return out

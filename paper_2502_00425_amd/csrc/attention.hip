@@ -1,0 +1,382 @@
+// Causal attention on AIFS-ordered tokens and rotary embedding with reordered
+// position ids, for gfx950 (MQuant, arXiv 2502.00425: Sec. 3.1, Eq. (5)-(6);
+// appendix "Rotary Position Embedding for AIFS").
+//
+// After the AIFS reorder a token's row index no longer says what it may attend.
+// Its original position does: token i attends token j exactly when
+// pos[j] <= pos[i] (the unified mask M^u[i,j] = M[pos[i], pos[j]] of the causal
+// M; for one visual segment this is the three-region rule of Eq. (6)).  The
+// kernel never materialises a [T,T] mask: it compares positions per element on
+// the tiles that need it, takes whole tiles unmasked or skips them by the
+// min/max of their positions, flash-attention style (online softmax, fp32
+// statistics, fp16 MFMA operands).
+#include <hip/hip_fp16.h>
+
+#include <climits>
+#include <cmath>
+
+#include "mquant_internal.h"
+
+using namespace mquant;
+
+namespace {
+
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kHeadDim = 128;          // the only head size built (28 x 128, 64 x 128 in the paper's models)
+constexpr int kBQ = 128;               // queries per work-group (32 per wave)
+constexpr int kBK = 64;                // keys per tile
+constexpr int kKPitch = 2 * kHeadDim + 16;   // bytes per key row in LDS: rows 4 banks apart
+constexpr int kVPitch = 2 * kBK + 8;         // bytes per V^T row (one head channel, 64 keys)
+
+// MFMA 32x32 result register r of lane group g holds row (r/4)*8 + g*4 + r%4.
+__device__ __forceinline__ int acc_row(int r, int g) { return (r >> 2) * 8 + g * 4 + (r & 3); }
+
+// ------------------------------------------------------------------- RoPE
+//
+// x'[2j] = x[2j] cos - x[2j+1] sin, x'[2j+1] = x[2j] sin + x[2j+1] cos with the
+// angle pos[i] * theta_j, theta_j = base^(-2j/D): the block-diagonal rotation
+// printed in the appendix, with the token's ORIGINAL position as its id.  The
+// angle and its sine/cosine are formed in double (a position of 16384 leaves an
+// fp32 angle accurate to 1e-3 only); one thread per (token, pair) serves all heads.
+struct InvFreq {
+    double f[kHeadDim / 2];
+};
+
+__global__ __launch_bounds__(256) void rope_kernel(__half *__restrict__ x, int64_t ldx,
+                                                   const int32_t *__restrict__ pos, int32_t T,
+                                                   int32_t n_heads, InvFreq inv)
+{
+    constexpr int P = kHeadDim / 2;
+    const int64_t total = static_cast<int64_t>(T) * P;
+    for (int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; e < total;
+         e += static_cast<int64_t>(gridDim.x) * 256) {
+        const int32_t i = static_cast<int32_t>(e / P);
+        const int32_t j = static_cast<int32_t>(e - static_cast<int64_t>(i) * P);
+        double sn, cs;
+        sincos(static_cast<double>(pos[i]) * inv.f[j], &sn, &cs);
+        const float c = static_cast<float>(cs), s = static_cast<float>(sn);
+        __half2 *row = reinterpret_cast<__half2 *>(x + static_cast<int64_t>(i) * ldx) + j;
+        for (int32_t h = 0; h < n_heads; ++h) {
+            const float2 v = __half22float2(row[h * P]);
+            row[h * P] = __floats2half2_rn(v.x * c - v.y * s, v.x * s + v.y * c);
+        }
+    }
+}
+
+// -------------------------------------------------------- V^T and tile bounds
+//
+// The P V product wants, per head channel, eight consecutive keys in one MFMA
+// operand register pair, so V goes through a one-off transpose
+// V[T][Hkv*D] -> Vt[Hkv*D][Tp] (Tp = T rounded up to the key tile, tail zeroed:
+// a zero probability times an uninitialised value could be NaN).  The same
+// launch records min and max position of every key tile.
+__global__ __launch_bounds__(256) void vt_kernel(const __half *__restrict__ v, int64_t ldv,
+                                                 __half *__restrict__ vt, int32_t T, int32_t Tp,
+                                                 int32_t channels, const int32_t *__restrict__ pos,
+                                                 int32_t *__restrict__ tile_min,
+                                                 int32_t *__restrict__ tile_max)
+{
+    __shared__ __half tile[64][66];
+    const int32_t t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) {
+        const int32_t t = t0 + r, c = c0 + tx;
+        tile[r][tx] = (t < T && c < channels) ? v[static_cast<int64_t>(t) * ldv + c] : __float2half(0.0f);
+    }
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4) {
+        const int32_t c = c0 + r, t = t0 + tx;
+        if (c < channels && t < Tp) vt[static_cast<int64_t>(c) * Tp + t] = tile[tx][r];
+    }
+    if (blockIdx.y == 0 && threadIdx.x < 64) {
+        const int32_t t = t0 + threadIdx.x;
+        int32_t lo = t < T ? pos[t] : INT_MAX, hi = t < T ? pos[t] : INT_MIN;
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            lo = min(lo, __shfl_xor(lo, m, 64));
+            hi = max(hi, __shfl_xor(hi, m, 64));
+        }
+        if (threadIdx.x == 0) {
+            tile_min[blockIdx.x] = lo;
+            tile_max[blockIdx.x] = hi;
+        }
+    }
+}
+
+// -------------------------------------------------------------- attention
+//
+// One work-group: 128 queries of one query head, four waves of 32 queries.
+// Per key tile (64 keys, shared through LDS):
+//   S^T = K Q^T     A = K rows (keys) from LDS, B = Q^T held in registers for the whole
+//                   kernel; in the result a LANE is a query, its registers are keys, so
+//                   the softmax statistics of a query live in one lane pair
+//   P^T             the same registers, as fp16, are the B operand of
+//   O^T += V^T P^T  A = V^T rows (head channels) from LDS; the result again has a lane per
+//                   query, so the running rescale needs no cross-lane traffic.
+// The next tile's K and V^T are requested from memory before the current tile is
+// computed and written to LDS after it.  Tiles whose smallest position exceeds the
+// group's largest query position are skipped altogether (no loads); a wave skips
+// the arithmetic of a tile that is masked for all of its 32 queries and drops the
+// per-element compare on tiles that are visible to all of them.
+__global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
+    const __half *__restrict__ q, int64_t ldq, const __half *__restrict__ k, int64_t ldk,
+    const __half *__restrict__ vt, int32_t Tp, __half *__restrict__ o, int64_t ldo,
+    const int32_t *__restrict__ pos, const int32_t *__restrict__ tile_min,
+    const int32_t *__restrict__ tile_max, int32_t T, int32_t group, float scale_log2e)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t k_lds[kBK * kKPitch];
+    __shared__ __attribute__((aligned(16))) uint8_t v_lds[kHeadDim * kVPitch];
+    __shared__ int32_t pos_lds[kBK];
+    __shared__ int32_t wg_qmax_lds[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int32_t head = blockIdx.y, kvh = head / group;
+    const int32_t q0 = blockIdx.x * kBQ + wave * 32;
+    const int32_t n_tiles = Tp / kBK;
+
+    // ---- this lane's query: position and Q^T fragments
+    const int32_t qi = q0 + l32;
+    const int32_t qrow = qi < T ? qi : T - 1;
+    const int32_t my_pos = pos[qrow];
+    v8h qf[kHeadDim / 16];
+    {
+        const __half *qp = q + static_cast<int64_t>(qrow) * ldq + head * kHeadDim + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < kHeadDim / 16; ++ks)
+            qf[ks] = *reinterpret_cast<const v8h *>(qp + ks * 16);
+    }
+    int32_t qmin = my_pos, qmax = my_pos;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        qmin = min(qmin, __shfl_xor(qmin, m, 64));
+        qmax = max(qmax, __shfl_xor(qmax, m, 64));
+    }
+    if (lane == 0) wg_qmax_lds[wave] = qmax;
+    __syncthreads();
+    const int32_t wg_qmax = max(max(wg_qmax_lds[0], wg_qmax_lds[1]), max(wg_qmax_lds[2], wg_qmax_lds[3]));
+
+    v16f acc_o[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[dt][r] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;
+
+    // ---- tile staging through registers: 4 chunks of K and 4 of V^T per thread
+    uint4 kreg[4];
+    uint2 vreg[8];
+    int32_t preg = 0;
+    const __half *kbase = k + kvh * kHeadDim;
+    const __half *vbase = vt + static_cast<int64_t>(kvh) * kHeadDim * Tp;
+    auto fetch = [&](int32_t t) {
+        const int32_t key0 = t * kBK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = tid + 256 * i, row = c >> 4, col = c & 15;
+            int32_t key = key0 + row;
+            key = key < T ? key : T - 1;
+            kreg[i] = *reinterpret_cast<const uint4 *>(kbase + static_cast<int64_t>(key) * ldk + col * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = tid + 256 * i, d = c >> 4, col = c & 15;          // 16 chunks of 4 keys per row
+            vreg[i] = *reinterpret_cast<const uint2 *>(vbase + static_cast<int64_t>(d) * Tp + key0 + col * 4);
+        }
+        if (tid < kBK) {
+            const int32_t key = key0 + tid;
+            preg = key < T ? pos[key] : INT_MAX;
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = tid + 256 * i, row = c >> 4, col = c & 15;
+            *reinterpret_cast<uint4 *>(k_lds + row * kKPitch + col * 16) = kreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = tid + 256 * i, d = c >> 4, col = c & 15;
+            *reinterpret_cast<uint2 *>(v_lds + d * kVPitch + col * 8) = vreg[i];
+        }
+        if (tid < kBK) pos_lds[tid] = preg;
+    };
+    auto next_tile = [&](int32_t t) {                     // first tile >= t the group needs, or n_tiles
+        while (t < n_tiles && tile_min[t] > wg_qmax) ++t;
+        return t;
+    };
+
+    int32_t t = next_tile(0);                              // tile of the group's own positions at the latest
+    fetch(t < n_tiles ? t : 0);
+    while (t < n_tiles) {
+        __syncthreads();                                   // every wave is done with the previous tile
+        stage();
+        __syncthreads();
+        const int32_t tn = next_tile(t + 1);
+        fetch(tn < n_tiles ? tn : t);                      // unconditional: the last one is a harmless re-read
+
+        const int32_t kmin = tile_min[t], kmax = tile_max[t];
+        const bool padded = (t + 1) * kBK > T;             // tile holds keys past the end
+        if (kmin <= qmax) {                                // else: masked for all 32 queries of the wave
+            // ---- S^T = K Q^T
+            v16f s[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kb][r] = 0.0f;
+                const uint8_t *krow = k_lds + (kb * 32 + l32) * kKPitch + g * 16;
+#pragma unroll
+                for (int ks = 0; ks < kHeadDim / 16; ++ks) {
+                    const v8h a = *reinterpret_cast<const v8h *>(krow + ks * 32);
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qf[ks], s[kb], 0, 0, 0);
+                }
+            }
+            // ---- scale (base-2 logits), mask, online softmax
+            const bool need_mask = kmax > qmin || padded;
+            float m_new = m_run;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float x = s[kb][r] * scale_log2e;
+                    if (need_mask && pos_lds[kb * 32 + acc_row(r, g)] > my_pos) x = -INFINITY;
+                    s[kb][r] = x;
+                    m_new = fmaxf(m_new, x);
+                }
+            m_new = fmaxf(m_new, __shfl_xor(m_new, 32, 64));     // the query's other 32 keys
+            const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // 0 while nothing was visible
+            float l_add = 0.0f;
+            v8h p[4];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float e = __builtin_amdgcn_exp2f(s[kb][r] - m_use);    // exp2(-inf) = 0
+                    l_add += e;
+                    p[kb * 2 + (r >> 3)][r & 7] = static_cast<_Float16>(e);
+                }
+            l_add += __shfl_xor(l_add, 32, 64);
+            l_run = l_run * alpha + l_add;
+            m_run = m_new;
+            // ---- O^T = O^T * alpha + V^T P^T
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha;
+                const uint8_t *vrow = v_lds + (dt * 32 + l32) * kVPitch + g * 8;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    // operand slot i of lane group g is key kk*16 + (i/4)*8 + g*4 + i%4
+                    const v4h lo = *reinterpret_cast<const v4h *>(vrow + kk * 32);
+                    const v4h hi = *reinterpret_cast<const v4h *>(vrow + kk * 32 + 16);
+                    v8h a;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        a[i] = lo[i];
+                        a[4 + i] = hi[i];
+                    }
+                    acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p[kk], acc_o[dt], 0, 0, 0);
+                }
+            }
+        }
+        t = tn;
+    }
+
+    // ---- normalise and store: lane = query, registers = head channels (4 consecutive per group)
+    if (qi < T) {
+        const float inv_l = 1.0f / l_run;                  // every token sees at least itself
+        __half *orow = o + static_cast<int64_t>(qi) * ldo + head * kHeadDim;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                __half h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h[e] = __float2half_rn(acc_o[dt][r4 * 4 + e] * inv_l);
+                *reinterpret_cast<uint2 *>(orow + dt * 32 + r4 * 8 + g * 4) = *reinterpret_cast<const uint2 *>(h);
+            }
+    }
+}
+
+int check_heads(int32_t T, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim)
+{
+    if (T < 0 || n_q_heads < 1 || n_kv_heads < 1) return MQUANT_ERR_BAD_SHAPE;
+    if (head_dim != kHeadDim) return MQUANT_ERR_UNSUPPORTED;
+    if (n_q_heads % n_kv_heads != 0) return MQUANT_ERR_BAD_SHAPE;
+    return MQUANT_OK;
+}
+
+int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+}  // namespace
+
+extern "C" int mquant_rope_apply(void *x, int64_t ldx, const int32_t *pos, int32_t T, int32_t n_heads,
+                                 int32_t head_dim, double base, mquant_stream_t stream)
+{
+    if (T < 0 || n_heads < 1) return MQUANT_ERR_BAD_SHAPE;
+    if (head_dim != kHeadDim) return MQUANT_ERR_UNSUPPORTED;
+    if (!(base > 1.0) || !std::isfinite(base)) return MQUANT_ERR_BAD_SHAPE;
+    if (T == 0) return MQUANT_OK;
+    if (!x || !pos) return MQUANT_ERR_NULL;
+    if (ldx < static_cast<int64_t>(n_heads) * head_dim) return MQUANT_ERR_BAD_SHAPE;
+    if (ldx % 2 != 0 || !aligned_to(x, 4) || !aligned_to(pos, 4)) return MQUANT_ERR_ALIGNMENT;
+    InvFreq inv;
+    for (int j = 0; j < kHeadDim / 2; ++j) inv.f[j] = pow(base, -2.0 * j / kHeadDim);
+    int64_t blocks = ceil_div(static_cast<int64_t>(T) * (kHeadDim / 2), 256);
+    if (blocks > 65536) blocks = 65536;
+    MQ_LAUNCH(rope_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
+              static_cast<hipStream_t>(stream), static_cast<__half *>(x), ldx, pos, T, n_heads, inv);
+    return launch_status();
+}
+
+extern "C" int64_t mquant_aifs_attention_workspace_bytes(int32_t T, int32_t n_kv_heads, int32_t head_dim)
+{
+    if (T < 0 || n_kv_heads < 1) return MQUANT_ERR_BAD_SHAPE;
+    if (head_dim != kHeadDim) return MQUANT_ERR_UNSUPPORTED;
+    const int64_t Tp = round_up(T, kBK);
+    const int64_t vt = round_up(static_cast<int64_t>(n_kv_heads) * head_dim * Tp * 2, 256);
+    return vt + round_up(2 * (Tp / kBK) * 4, 256);
+}
+
+extern "C" int mquant_aifs_attention(const void *q, int64_t ldq, const void *k, int64_t ldk,
+                                     const void *v, int64_t ldv, void *o, int64_t ldo,
+                                     const int32_t *pos, int32_t T, int32_t n_q_heads,
+                                     int32_t n_kv_heads, int32_t head_dim, void *workspace,
+                                     int64_t workspace_bytes, mquant_stream_t stream_)
+{
+    const int st = check_heads(T, n_q_heads, n_kv_heads, head_dim);
+    if (st != MQUANT_OK) return st;
+    if (T == 0) return MQUANT_OK;
+    if (!q || !k || !v || !o || !pos) return MQUANT_ERR_NULL;
+    const int64_t qw = static_cast<int64_t>(n_q_heads) * head_dim, kw = static_cast<int64_t>(n_kv_heads) * head_dim;
+    if (ldq < qw || ldo < qw || ldk < kw || ldv < kw) return MQUANT_ERR_BAD_SHAPE;
+    if (ldq % 8 != 0 || ldk % 8 != 0 || ldo % 4 != 0 || !aligned_to(q, 16) || !aligned_to(k, 16) ||
+        !aligned_to(v, 2) || !aligned_to(o, 8) || !aligned_to(pos, 4))
+        return MQUANT_ERR_ALIGNMENT;
+    const int64_t need = mquant_aifs_attention_workspace_bytes(T, n_kv_heads, head_dim);
+    if (!workspace || workspace_bytes < need) return MQUANT_ERR_WORKSPACE;
+    if (!aligned_to(workspace, 256)) return MQUANT_ERR_ALIGNMENT;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+
+    const int32_t Tp = static_cast<int32_t>(round_up(T, kBK));
+    const int32_t n_tiles = Tp / kBK;
+    __half *vt = static_cast<__half *>(workspace);
+    int32_t *tile_min = reinterpret_cast<int32_t *>(
+        static_cast<uint8_t *>(workspace) + round_up(kw * Tp * 2, 256));
+    int32_t *tile_max = tile_min + n_tiles;
+    MQ_LAUNCH(vt_kernel, dim3(n_tiles, static_cast<unsigned>(ceil_div(kw, 64))), dim3(256), 0, stream,
+              static_cast<const __half *>(v), ldv, vt, T, Tp, static_cast<int32_t>(kw), pos, tile_min,
+              tile_max);
+    int ls = launch_status();
+    if (ls != MQUANT_OK) return ls;
+    const float scale_log2e = static_cast<float>(1.4426950408889634 / sqrt(static_cast<double>(head_dim)));
+    MQ_LAUNCH(aifs_attention_kernel, dim3(static_cast<unsigned>(ceil_div(T, kBQ)), n_q_heads), dim3(256),
+              0, stream, static_cast<const __half *>(q), ldq, static_cast<const __half *>(k), ldk, vt, Tp,
+              static_cast<__half *>(o), ldo, pos, tile_min, tile_max, T, n_q_heads / n_kv_heads,
+              scale_log2e);
+    return launch_status();
+}

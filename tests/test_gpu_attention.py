@@ -1,0 +1,166 @@
+"""GPU parity of the AIFS attention kernel and the rotary embedding with reordered
+position ids against the fp64 oracle.
+
+Tolerance of the attention output (derived from the arithmetic): probabilities are
+rounded to fp16 before the P V product (relative 2^-11 each, the weights of a query
+sum to one -> at most 2^-11 max|v| in the output), the output is rounded to fp16
+(2^-11 |o| <= 2^-11 max|v|), logits and the softmax statistics are fp32 (1e-6
+relative, negligible).  Bound used: 2.5 * 2^-11 * max|v| ~ 1.2e-3 max|v|.
+RoPE: sines and cosines in double on both sides, products in fp32, fp16 result:
+2^-11 relative to the pair's magnitude, bound 1e-3 * |pair|."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import mquant_oracle as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mq():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2502_00425_amd import binding
+    return binding
+
+
+def say(msg):
+    print(f"[parity-attn] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def make_qkv(rng, T, Hq, Hkv, D=128, q_gain=1.0):
+    q = (rng.standard_normal((T, Hq * D)) * q_gain).astype(np.float16)
+    k = rng.standard_normal((T, Hkv * D)).astype(np.float16)
+    v = (rng.standard_normal((T, Hkv * D)) * 2.0).astype(np.float16)
+    return q, k, v
+
+
+def check_attention(mq, q, k, v, pos, Hq, Hkv, rows=None, what=""):
+    got = mq.aifs_attention(dev(q), dev(k), dev(v), dev(pos.astype(np.int32)), Hq, Hkv).cpu().numpy()
+    ref = orc.aifs_attention_f64(q, k, v, pos, Hq, Hkv, rows=rows)
+    if rows is not None:
+        got = got[np.asarray(rows)]
+    tol = 2.5 * 2.0 ** -11 * float(np.abs(v.astype(np.float64)).max())
+    err = np.abs(got.astype(np.float64) - ref)
+    assert np.isfinite(got).all(), what
+    assert err.max() <= tol, f"{what}: max error {err.max():.3e} > {tol:.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+@pytest.mark.parametrize("T,spans,Hq,Hkv", [
+    (64, [(8, 48)], 2, 1),                       # one key tile, configs[0] layout
+    (1, [], 1, 1),
+    (37, [(0, 5)], 2, 2),                        # ragged, visual first already
+    (200, [(16, 100)], 4, 2),                    # several tiles, ragged tail
+    (301, [(5, 100), (150, 7), (290, 11)], 3, 1),  # several visual spans, visual at the very end
+    (256, [], 2, 1),                             # text only: plain causal
+    (256, [(0, 256)], 2, 1),                     # visual only
+])
+def test_attention_small_full(mq, T, spans, Hq, Hkv):
+    say(f"attention T={T} spans={spans}")
+    rng = np.random.default_rng(T + Hq)
+    q, k, v = make_qkv(rng, T, Hq, Hkv, q_gain=0.5)
+    perm, _, _ = orc.aifs_build_perm(T, spans)
+    check_attention(mq, q[perm], k[perm], v[perm], perm, Hq, Hkv, what=f"T={T}")
+
+
+def test_attention_peaked_softmax_and_ties(mq):
+    """Large logits (one key dominates) and repeated positions (ties attend each other)."""
+    say("attention peaked / ties")
+    rng = np.random.default_rng(3)
+    T, Hq, Hkv = 130, 2, 1
+    q, k, v = make_qkv(rng, T, Hq, Hkv, q_gain=4.0)
+    pos = rng.integers(0, 20, size=T)
+    check_attention(mq, q, k, v, pos, Hq, Hkv, what="ties")
+
+
+def test_attention_is_invariant_under_the_reorder_on_the_gpu(mq):
+    """The claim AIFS is named for, end to end on the device: reordered tokens with the
+    position rule give the outputs of the original order, row for row."""
+    say("attention invariance")
+    rng = np.random.default_rng(4)
+    T, Hq, Hkv = 192, 2, 1
+    q, k, v = make_qkv(rng, T, Hq, Hkv, q_gain=0.5)
+    perm, _, _ = orc.aifs_build_perm(T, [(10, 90), (130, 20)])
+    a = mq.aifs_attention(dev(q), dev(k), dev(v), dev(np.arange(T, dtype=np.int32)), Hq, Hkv).cpu().numpy()
+    b = mq.aifs_attention(dev(q[perm]), dev(k[perm]), dev(v[perm]), dev(perm.astype(np.int32)), Hq, Hkv).cpu().numpy()
+    tol = 2 * 2.5 * 2.0 ** -11 * float(np.abs(v.astype(np.float64)).max())
+    assert np.abs(a[perm].astype(np.float64) - b.astype(np.float64)).max() <= tol
+
+
+def test_attention_strided_views_of_a_qkv_buffer(mq):
+    """q, k, v as column slices of one [T, (Hq + 2 Hkv) D] projection output."""
+    say("attention strided")
+    rng = np.random.default_rng(5)
+    T, Hq, Hkv, D = 100, 4, 1, 128
+    q, k, v = make_qkv(rng, T, Hq, Hkv, q_gain=0.5)
+    perm, _, _ = orc.aifs_build_perm(T, [(20, 50)])
+    buf = dev(np.concatenate([q[perm], k[perm], v[perm]], axis=1))
+    got = mq.aifs_attention(buf[:, :Hq * D], buf[:, Hq * D:(Hq + Hkv) * D], buf[:, (Hq + Hkv) * D:],
+                            dev(perm.astype(np.int32)), Hq, Hkv).cpu().numpy()
+    ref = orc.aifs_attention_f64(q[perm], k[perm], v[perm], perm, Hq, Hkv)
+    tol = 2.5 * 2.0 ** -11 * float(np.abs(v.astype(np.float64)).max())
+    assert np.abs(got.astype(np.float64) - ref).max() <= tol
+
+
+def test_attention_config2_layout_sampled(mq):
+    """configs[2]: T = 4096 (visual 256..3839), 28 query heads on 4 key/value heads; sampled rows."""
+    say("attention c2 sampled")
+    rng = np.random.default_rng(6)
+    T, Hq, Hkv = 4096, 28, 4
+    q, k, v = make_qkv(rng, T, Hq, Hkv, q_gain=0.3)
+    perm, _, V = orc.aifs_build_perm(T, [(256, 3584)])
+    rows = np.unique(np.r_[0, 1, 127, 128, V - 1, V, V + 1, V + 255, V + 256, T - 1, rng.choice(T, 20, replace=False)])
+    check_attention(mq, q[perm], k[perm], v[perm], perm, Hq, Hkv, rows=rows, what="c2")
+
+
+def test_attention_argument_errors(mq):
+    x = torch.zeros((4, 128), dtype=torch.float16, device="cuda")
+    pos = torch.zeros(4, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    call = lambda hq, hkv, d, wsp, wsb: mq.lib.mquant_aifs_attention(
+        x.data_ptr(), 128, x.data_ptr(), 128, x.data_ptr(), 128, x.data_ptr(), 128, pos.data_ptr(), 4,
+        hq, hkv, d, wsp, wsb, None)
+    assert call(1, 1, 64, ws.data_ptr(), 1 << 16) == mq.ERR_UNSUPPORTED
+    assert call(3, 2, 128, ws.data_ptr(), 1 << 16) == mq.ERR_BAD_SHAPE
+    assert call(1, 1, 128, None, 0) == mq.ERR_WORKSPACE
+    assert call(2, 1, 128, ws.data_ptr(), 1 << 16) == mq.ERR_BAD_SHAPE      # ldq < 2 * 128
+    assert call(1, 1, 128, ws.data_ptr(), 1 << 16) == mq.OK
+    torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------- RoPE
+
+@pytest.mark.parametrize("T,H", [(1, 1), (77, 4), (1280, 32)])
+def test_rope_matches_oracle(mq, T, H):
+    say(f"rope T={T} H={H}")
+    rng = np.random.default_rng(T + H)
+    D = 128
+    x = rng.standard_normal((T, H * D)).astype(np.float16)
+    perm, _, _ = orc.aifs_build_perm(T, [(T // 5, T // 2)]) if T > 4 else (np.arange(T), None, 0)
+    pos = perm.astype(np.int64) * (16000 // max(T, 1) if T > 1 else 1)      # positions up to ~16000
+    xd = dev(x[perm])
+    mq.rope_apply(xd, dev(pos.astype(np.int32)), H)
+    got = xd.cpu().numpy().astype(np.float64)
+    ref = orc.rope_apply_f64(x[perm], pos, H)
+    mag = np.sqrt((ref.reshape(T, H, D // 2, 2) ** 2).sum(-1))
+    err = np.abs(got - ref).reshape(T, H, D // 2, 2).max(-1)
+    assert (err <= 1e-3 * np.maximum(mag, 2.0 ** -14)).all()
+
+
+def test_rope_leaves_the_rest_of_the_row_alone(mq):
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((10, 3 * 128)).astype(np.float16)
+    xd = dev(x)
+    mq.rope_apply(xd, dev(np.arange(10, dtype=np.int32)), 2)        # rotate the first two heads only
+    got = xd.cpu().numpy()
+    assert (got[:, 256:] == x[:, 256:]).all()
+    assert (got[0] == x[0]).all()                                   # position 0: identity
+    assert not (got[1:, :256] == x[1:, :256]).all()
