@@ -45,6 +45,7 @@ def parse_args():
     ap.add_argument("--decode-layers", type=int, default=28)
     ap.add_argument("--decode-iters", type=int, default=10)
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-attention", action="store_true", help="skip the attention / RoPE leg")
     ap.add_argument("--no-rms", action="store_true", help="skip the RMS split-path leg")
     ap.add_argument("--no-dynamic", action="store_true", help="skip the per-token dynamic baseline leg")
     ap.add_argument("--no-graphs", action="store_true",
@@ -331,6 +332,10 @@ def main():
         rms.update({k: round(v, 2) for k, v in best.items()})
         result["rms_split"] = rms
 
+    # ----------------------------- AIFS attention + rotary embedding (context, next row 2)
+    if not args.no_attention:
+        result["attention"] = bench_attention(args, torch, mq, wl, np)
+
     # ------------------------------------------------------------------ decode
     if not args.no_decode:
         result["decode"] = bench_decode(args, torch, mq, wl)
@@ -340,6 +345,61 @@ def main():
         result["cpu_baseline"] = cpu_baseline(args, np, w, lin, V)
 
     print(json.dumps(result), flush=True)
+
+
+def bench_attention(args, torch, mq, wl, np):
+    """Attention on AIFS-ordered tokens (28 query heads on 4 key/value heads of 128 channels,
+    the 7B shapes) for the layouts of configs[1] and configs[2]; q, k, v are column slices of
+    one [T, 4608] buffer as the qkv projection leaves them.  Algorithmic flops: 4*D per
+    allowed (query, key) pair and query head; peak: dense fp16 MFMA 2.5 PFLOP/s."""
+    out = {"unit": "TFLOP/s", "peak": 2500.0, "bound": "mfma (fp16)", "per_config": {}}
+    Hq, Hkv, D = 28, 4, 128
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4000)
+    for cfg in (1, 2):
+        w = wl.workload(cfg)
+        T = w.T
+        perm, _, V = mq.aifs_build_perm(T, list(w.vis_spans))
+        pos = torch.from_numpy(np.ascontiguousarray(perm)).cuda()
+        qkv = (torch.randn((T, (Hq + 2 * Hkv) * D), device="cuda", generator=gen) * 0.5).half()
+        q, k, v = qkv[:, :Hq * D], qkv[:, Hq * D:(Hq + Hkv) * D], qkv[:, (Hq + Hkv) * D:]
+        ws = torch.empty(mq.aifs_attention_workspace_bytes(T, Hkv), dtype=torch.uint8, device="cuda")
+        o = torch.empty((T, Hq * D), dtype=torch.float16, device="cuda")
+
+        def timed(fn, n=10):
+            fn()
+            torch.cuda.synchronize()
+            run, reps = fn, n
+            if not args.no_graphs:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for _ in range(n):
+                        fn()
+                run, reps = g.replay, 1
+                run()
+                torch.cuda.synchronize()
+            best = float("inf")
+            for _ in range(3):
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    run()
+                e1.record()
+                e1.synchronize()
+                best = min(best, e0.elapsed_time(e1) / n)
+            return best
+
+        ms = timed(lambda: mq.aifs_attention(q, k, v, pos, Hq, Hkv, out=o, workspace=ws))
+        pairs = T * (T + 1) // 2                      # allowed pairs of a causal mask in any order
+        flops = 4.0 * D * pairs * Hq
+        ms_rope = timed(lambda: mq.rope_apply(qkv[:, :(Hq + Hkv) * D], pos, Hq + Hkv))
+        rope_bytes = 4.0 * T * (Hq + Hkv) * D
+        out["per_config"]["configs[%d] T=%d" % (cfg, T)] = {
+            "attention_us": round(ms * 1e3, 1), "TFLOPs": round(flops / ms / 1e9, 1),
+            "frac": round(flops / ms / 1e9 / 2500.0, 4),
+            "rope_us": round(ms_rope * 1e3, 2), "rope_GBps": round(rope_bytes / ms_rope / 1e6, 1)}
+    return out
 
 
 def bench_decode(args, torch, mq, wl):
