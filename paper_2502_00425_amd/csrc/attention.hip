@@ -24,6 +24,8 @@ namespace {
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
 constexpr int kHeadDim = 128;          // the only head size built (28 x 128, 64 x 128 in the paper's models)
 constexpr int kBQ = 128;               // queries per work-group (32 per wave)
@@ -167,8 +169,8 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
     float m_run = -INFINITY, l_run = 0.0f;
 
     // ---- tile staging through registers: 4 chunks of K and 4 of V^T per thread
-    uint4 kreg[4];
-    uint2 vreg[8];
+    v4u kreg[4];                                           // native vectors: HIP's uint4 struct
+    v2u vreg[8];                                           // ends up in scratch here
     int32_t preg = 0;
     const __half *kbase = k + kvh * kHeadDim;
     const __half *vbase = vt + static_cast<int64_t>(kvh) * kHeadDim * Tp;
@@ -179,12 +181,12 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
             const int c = tid + 256 * i, row = c >> 4, col = c & 15;
             int32_t key = key0 + row;
             key = key < T ? key : T - 1;
-            kreg[i] = *reinterpret_cast<const uint4 *>(kbase + static_cast<int64_t>(key) * ldk + col * 8);
+            kreg[i] = *reinterpret_cast<const v4u *>(kbase + static_cast<int64_t>(key) * ldk + col * 8);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int c = tid + 256 * i, d = c >> 4, col = c & 15;          // 16 chunks of 4 keys per row
-            vreg[i] = *reinterpret_cast<const uint2 *>(vbase + static_cast<int64_t>(d) * Tp + key0 + col * 4);
+            vreg[i] = *reinterpret_cast<const v2u *>(vbase + static_cast<int64_t>(d) * Tp + key0 + col * 4);
         }
         if (tid < kBK) {
             const int32_t key = key0 + tid;
@@ -195,12 +197,12 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int c = tid + 256 * i, row = c >> 4, col = c & 15;
-            *reinterpret_cast<uint4 *>(k_lds + row * kKPitch + col * 16) = kreg[i];
+            *reinterpret_cast<v4u *>(k_lds + row * kKPitch + col * 16) = kreg[i];
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int c = tid + 256 * i, d = c >> 4, col = c & 15;
-            *reinterpret_cast<uint2 *>(v_lds + d * kVPitch + col * 8) = vreg[i];
+            *reinterpret_cast<v2u *>(v_lds + d * kVPitch + col * 8) = vreg[i];
         }
         if (tid < kBK) pos_lds[tid] = preg;
     };
@@ -224,28 +226,39 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
             // ---- S^T = K Q^T
             v16f s[2];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[kb][r] = 0.0f;
-                const uint8_t *krow = k_lds + (kb * 32 + l32) * kKPitch + g * 16;
+            // the two key blocks alternate: a dependent MFMA pair back to back waits out the pipe
 #pragma unroll
-                for (int ks = 0; ks < kHeadDim / 16; ++ks) {
-                    const v8h a = *reinterpret_cast<const v8h *>(krow + ks * 32);
+            for (int ks = 0; ks < kHeadDim / 16; ++ks)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const v8h a = *reinterpret_cast<const v8h *>(
+                        k_lds + (kb * 32 + l32) * kKPitch + g * 16 + ks * 32);
                     s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qf[ks], s[kb], 0, 0, 0);
                 }
-            }
             // ---- scale (base-2 logits), mask, online softmax
             const bool need_mask = kmax > qmin || padded;
             float m_new = m_run;
+            if (need_mask) {                               // wave-uniform
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const bool hidden = pos_lds[kb * 32 + acc_row(r, g)] > my_pos;
+                        s[kb][r] = hidden ? -INFINITY : s[kb][r] * scale_log2e;
+                    }
+            } else {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[kb][r] *= scale_log2e;
+            }
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float x = s[kb][r] * scale_log2e;
-                    if (need_mask && pos_lds[kb * 32 + acc_row(r, g)] > my_pos) x = -INFINITY;
-                    s[kb][r] = x;
-                    m_new = fmaxf(m_new, x);
-                }
+                for (int r = 0; r < 16; ++r) m_new = fmaxf(m_new, s[kb][r]);
             m_new = fmaxf(m_new, __shfl_xor(m_new, 32, 64));     // the query's other 32 keys
             const float m_use = m_new == -INFINITY ? 0.0f : m_new;
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // 0 while nothing was visible
@@ -262,17 +275,19 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
             l_add += __shfl_xor(l_add, 32, 64);
             l_run = l_run * alpha + l_add;
             m_run = m_new;
-            // ---- O^T = O^T * alpha + V^T P^T
+            // ---- O^T = O^T * alpha + V^T P^T (the four channel blocks alternate)
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
+            for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha;
-                const uint8_t *vrow = v_lds + (dt * 32 + l32) * kVPitch + g * 8;
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
                     // operand slot i of lane group g is key kk*16 + (i/4)*8 + g*4 + i%4
-                    const v4h lo = *reinterpret_cast<const v4h *>(vrow + kk * 32);
-                    const v4h hi = *reinterpret_cast<const v4h *>(vrow + kk * 32 + 16);
+                    const uint8_t *vrow = v_lds + (dt * 32 + l32) * kVPitch + g * 8 + kk * 32;
+                    const v4h lo = *reinterpret_cast<const v4h *>(vrow);
+                    const v4h hi = *reinterpret_cast<const v4h *>(vrow + 16);
                     v8h a;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
@@ -281,7 +296,6 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
                     }
                     acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p[kk], acc_o[dt], 0, 0, 0);
                 }
-            }
         }
         t = tn;
     }
