@@ -188,6 +188,27 @@ void orc_dequant_rms_f32(const int32_t *acc, const int8_t *xq, int64_t T, int64_
     }
 }
 
+/*
+ * Eq. (2)/(3) at another activation bit-width b (the W4A4 setting of the
+ * accuracy tables: b = 4, codes in [-8, 7]): as orc_msq_quantize with the clamp
+ * range [-2^(b-1), 2^(b-1)-1].  The codes still occupy one int8 each.
+ */
+void orc_msq_quantize_bits(const float *u, int64_t T, int64_t K, int64_t V,
+                           float c_vis, float c_txt, int32_t bits, int8_t *xq)
+{
+    const float hi = (float)((1 << (bits - 1)) - 1), lo = -(float)(1 << (bits - 1));
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < T; ++i) {
+        const float c = (i < V) ? c_vis : c_txt;
+        for (int64_t k = 0; k < K; ++k) {
+            float r = nearbyintf(u[i * K + k] * c);
+            if (r < lo) r = lo;
+            if (r > hi) r = hi;
+            xq[i * K + k] = (int8_t)r;
+        }
+    }
+}
+
 /* max |u| over a [T,K] fp32 matrix (calibration statistic, Eq. (2)'s max|x|). */
 float orc_absmax_f32(const float *u, int64_t n)
 {

@@ -43,6 +43,7 @@ def _lib() -> ctypes.CDLL:
         lib.orc_fwht_block_f32.argtypes = [p, i32]
         lib.orc_hadamard_rows_f32.argtypes = [p, i64, i64, i32]
         lib.orc_msq_quantize.argtypes = [p, i64, i64, i64, f32, f32, p]
+        lib.orc_msq_quantize_bits.argtypes = [p, i64, i64, i64, f32, f32, i32, p]
         lib.orc_absmax_f32.argtypes = [p, i64]
         lib.orc_absmax_f32.restype = f32
         lib.orc_unpack_w4.argtypes = [p, i64, i64, p]
@@ -263,6 +264,24 @@ def msq_quantize(u: np.ndarray, V: int, s_vis: float, s_txt: float, B: int) -> n
     _lib().orc_msq_quantize(_ptr(u), T, K, V,
                             quant_multiplier(s_vis, B), quant_multiplier(s_txt, B), _ptr(xq))
     return xq
+
+
+def msq_quantize_bits(u: np.ndarray, V: int, s_vis: float, s_txt: float, B: int, bits: int) -> np.ndarray:
+    """msq_quantize at activation bit-width `bits` (Eq. (2) with b = bits; W4A4 is
+    bits = 4, codes in [-8, 7]); one int8 per code."""
+    if not 2 <= bits <= 8:
+        raise ValueError("bits must be in 2..8")
+    u = _c(u, np.float32)
+    T, K = u.shape
+    xq = np.empty((T, K), dtype=np.int8)
+    _lib().orc_msq_quantize_bits(_ptr(u), T, K, V, quant_multiplier(s_vis, B),
+                                 quant_multiplier(s_txt, B), bits, _ptr(xq))
+    return xq
+
+
+def static_scale_from_absmax_bits(absmax_u: float, B: int, bits: int) -> np.float32:
+    """s = max|x_rot| / (2^{b-1} - 1) of Eq. (2) for bit-width b."""
+    return np.float32(float(np.float32(absmax_u)) / math.sqrt(float(B)) / float((1 << (bits - 1)) - 1))
 
 
 def rotated_absmax(x_calib: np.ndarray, B: int) -> np.float32:

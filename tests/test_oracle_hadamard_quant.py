@@ -232,3 +232,34 @@ def test_quantized_rotation_reconstructs_input():
         err = rec - x[:, b * B:(b + 1) * B].astype(np.float64)
         assert np.abs(err).max() < float(s) * 0.5 * math.sqrt(B) * 0.5
         assert np.sqrt((err ** 2).mean()) < float(s) / math.sqrt(12) * 1.2
+
+
+# ------------------------------------------------- other activation bit-widths
+
+def test_a4_quantizer_hand_computed_codes(golden_dir):
+    xs, codes = [], []
+    with open(os.path.join(golden_dir, "quant_a4_exact_multiples.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                a, b = line.split()
+                xs.append(float(a))
+                codes.append(int(b))
+    u = orc.hadamard_rotate(np.array(xs, dtype=np.float16).reshape(1, -1), 1)
+    got = orc.msq_quantize_bits(u, 0, 999.0, 0.5, 1, 4)
+    assert (got[0] == np.array(codes)).all()
+    assert got.min() == -8 and got.max() == 7
+
+
+def test_bits_8_is_the_int8_quantizer_and_narrower_is_its_clamp():
+    rng = np.random.default_rng(21)
+    u = (rng.standard_normal((7, 128)) * 40).astype(np.float32)
+    a = orc.msq_quantize(u, 3, 0.9, 0.11, 64)
+    assert (orc.msq_quantize_bits(u, 3, 0.9, 0.11, 64, 8) == a).all()
+    for bits in (2, 4, 6):
+        lo, hi = -(1 << (bits - 1)), (1 << (bits - 1)) - 1
+        assert (orc.msq_quantize_bits(u, 3, 0.9, 0.11, 64, bits) == np.clip(a, lo, hi)).all()
+    # scale of Eq. (2) for b = 4: the largest rotated magnitude lands on 7
+    s4 = orc.static_scale_from_absmax_bits(np.abs(u).max(), 64, 4)
+    q4 = orc.msq_quantize_bits(u, 0, s4, s4, 64, 4)
+    assert np.abs(q4.astype(np.int64)).max() == 7
