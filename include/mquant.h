@@ -138,6 +138,18 @@ int mquant_hadamard_quant_act(const void *x_dev, int64_t ldx, const int32_t *per
                               mquant_stream_t stream);
 
 /*
+ * DEVICE.  mquant_hadamard_quant_act at activation bit-width act_bits in 2..8
+ * (Eq. (2) with b = act_bits; the W4A4 setting of the accuracy tables is
+ * act_bits = 4, codes in [-8, 7]).  The codes still take one int8 each, so the
+ * GEMM / GEMV entry points consume them unchanged.  act_bits = 8 is
+ * mquant_hadamard_quant_act.  ERR_UNSUPPORTED for act_bits outside 2..8.
+ */
+int mquant_hadamard_quant_act_bits(const void *x_dev, int64_t ldx, const int32_t *perm_dev,
+                                   int8_t *xq_dev, int32_t T, int32_t K, int32_t n_vis,
+                                   float s_vis, float s_txt, int32_t had_block, int32_t act_bits,
+                                   mquant_stream_t stream);
+
+/*
  * DEVICE.  Calibration statistic of Algorithm 1 (activation scale from
  * calibration samples; Eq. (2): s = max|x| / 127): the maximum |u| over the
  * unnormalised rotation of all T rows, combined into *absmax_dev with max().

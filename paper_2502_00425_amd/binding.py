@@ -29,6 +29,7 @@ EXPORTS = (
     "mquant_w4a8_gemm", "mquant_w4a8_linear_prefill_workspace_bytes", "mquant_w4a8_linear_prefill",
     "mquant_hadamard_dynquant_act", "mquant_w4a8_gemm_rowscale", "mquant_w4a8_gemm_rms",
     "mquant_rope_apply", "mquant_aifs_attention_workspace_bytes", "mquant_aifs_attention",
+    "mquant_hadamard_quant_act_bits",
 )
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGNMENT = 0, -1, -2, -3, -4, -5, -6
@@ -59,6 +60,7 @@ def _load() -> ctypes.CDLL:
     lib.mquant_aifs_remap_mask.argtypes = [p, p, p, i32, p]
     lib.mquant_hadamard_quant_act.argtypes = [p, i64, p, p, i32, i32, i32, f32, f32, i32, p]
     lib.mquant_hadamard_absmax.argtypes = [p, i64, i32, i32, i32, p, p]
+    lib.mquant_hadamard_quant_act_bits.argtypes = [p, i64, p, p, i32, i32, i32, f32, f32, i32, i32, p]
     lib.mquant_hadamard_dynquant_act.argtypes = [p, i64, p, p, p, i32, i32, i32, p]
     lib.mquant_w4a8_gemm_rowscale.argtypes = [p, p, p, p, p, i64, p, i32, i32, i32, p, i64, p]
     lib.mquant_w4a8_gemm_rms.argtypes = [p, p, p, p, i64, p, i32, i32, i32, i32, f32, f32, p, p, p, i32,
@@ -152,15 +154,20 @@ def aifs_remap_mask(mask, perm_dev, out=None):
 
 
 def hadamard_quant_act(x, n_vis: int, s_vis: float, s_txt: float, had_block: int,
-                       perm_dev=None, out=None, T: Optional[int] = None):
+                       perm_dev=None, out=None, T: Optional[int] = None, act_bits: Optional[int] = None):
     import torch
     rows, K = x.shape
     T = rows if T is None else T
     if out is None:
         out = torch.empty((T, K), dtype=torch.int8, device=x.device)
-    _check(lib.mquant_hadamard_quant_act(_dp(x), x.stride(0), _dp(perm_dev), _dp(out), T, K, n_vis,
-                                         s_vis, s_txt, had_block, _stream()),
-           "mquant_hadamard_quant_act")
+    if act_bits is None:
+        _check(lib.mquant_hadamard_quant_act(_dp(x), x.stride(0), _dp(perm_dev), _dp(out), T, K, n_vis,
+                                             s_vis, s_txt, had_block, _stream()),
+               "mquant_hadamard_quant_act")
+    else:
+        _check(lib.mquant_hadamard_quant_act_bits(_dp(x), x.stride(0), _dp(perm_dev), _dp(out), T, K,
+                                                  n_vis, s_vis, s_txt, had_block, act_bits, _stream()),
+               "mquant_hadamard_quant_act_bits")
     return out
 
 

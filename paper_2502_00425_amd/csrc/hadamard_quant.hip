@@ -189,7 +189,8 @@ struct Segment {
     }
 
     // int8 codes clamp(rne(v * cmul)) of this segment into row `xq_row`.
-    __device__ __forceinline__ void quant_store(float cmul, int8_t *xq_row, int32_t sidx, int lane) const
+    __device__ __forceinline__ void quant_store(float cmul, int8_t *xq_row, int32_t sidx, int lane,
+                                                float q_lo = -128.0f, float q_hi = 127.0f) const
     {
 #pragma unroll
         for (int c = 0; c < C; ++c) {
@@ -200,7 +201,7 @@ struct Segment {
                 uint32_t bits[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const float t = __builtin_amdgcn_fmed3f(v[c][j] * cmul, -128.0f, 127.0f);
+                    const float t = __builtin_amdgcn_fmed3f(v[c][j] * cmul, q_lo, q_hi);
                     bits[j] = __float_as_uint(t + 12582912.0f);
                 }
                 uint32_t packed[2];
@@ -222,7 +223,7 @@ template <int B, bool ABSMAX>
 __global__ __launch_bounds__(256) void hadamard_quant_kernel(
     const __half *__restrict__ x, int64_t ldx, const int32_t *__restrict__ perm,
     int8_t *__restrict__ xq, int32_t T, int32_t K, int32_t n_vis, float c_vis, float c_txt,
-    int32_t segs_per_row, float *__restrict__ absmax)
+    int32_t segs_per_row, float *__restrict__ absmax, float q_lo, float q_hi)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t wave0 = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
@@ -242,7 +243,8 @@ __global__ __launch_bounds__(256) void hadamard_quant_kernel(
         if constexpr (ABSMAX) {
             wave_max = sg.absmax(wave_max);
         } else {
-            sg.quant_store((i < n_vis) ? c_vis : c_txt, xq + static_cast<int64_t>(i) * K, sidx, lane);
+            sg.quant_store((i < n_vis) ? c_vis : c_txt, xq + static_cast<int64_t>(i) * K, sidx, lane,
+                           q_lo, q_hi);
         }
     }
 
@@ -310,7 +312,8 @@ __global__ __launch_bounds__(256) void hadamard_dynquant_kernel(
 
 template <bool ABSMAX>
 int launch(const void *x, int64_t ldx, const int32_t *perm, int8_t *xq, int32_t T, int32_t K,
-           int32_t n_vis, float c_vis, float c_txt, int32_t B, float *absmax, hipStream_t stream)
+           int32_t n_vis, float c_vis, float c_txt, int32_t B, float *absmax, hipStream_t stream,
+           int32_t bits = 8)
 {
     const int32_t seg = B > 512 ? B : 512;
     const int32_t segs_per_row = static_cast<int32_t>(ceil_div(K, seg));
@@ -319,10 +322,12 @@ int launch(const void *x, int64_t ldx, const int32_t *perm, int8_t *xq, int32_t 
     if (blocks > (1 << 20)) blocks = 1 << 20;
     const dim3 grid(static_cast<unsigned>(blocks)), block(256);
     const __half *xh = static_cast<const __half *>(x);
+    const float q_hi = static_cast<float>((1 << (bits - 1)) - 1), q_lo = -static_cast<float>(1 << (bits - 1));
 #define MQ_CASE(BV)                                                                          \
     case BV:                                                                                 \
         MQ_LAUNCH((hadamard_quant_kernel<BV, ABSMAX>), grid, block, 0, stream, xh,  \
-                           ldx, perm, xq, T, K, n_vis, c_vis, c_txt, segs_per_row, absmax);  \
+                           ldx, perm, xq, T, K, n_vis, c_vis, c_txt, segs_per_row, absmax,   \
+                           q_lo, q_hi);                                                      \
         break;
     switch (B) {
         MQ_CASE(1) MQ_CASE(2) MQ_CASE(4) MQ_CASE(8) MQ_CASE(16) MQ_CASE(32) MQ_CASE(64)
@@ -352,6 +357,16 @@ extern "C" int mquant_hadamard_quant_act(const void *x, int64_t ldx, const int32
                                          float s_vis, float s_txt, int32_t had_block,
                                          mquant_stream_t stream)
 {
+    return mquant_hadamard_quant_act_bits(x, ldx, perm, xq, T, K, n_vis, s_vis, s_txt, had_block, 8,
+                                          stream);
+}
+
+extern "C" int mquant_hadamard_quant_act_bits(const void *x, int64_t ldx, const int32_t *perm,
+                                              int8_t *xq, int32_t T, int32_t K, int32_t n_vis,
+                                              float s_vis, float s_txt, int32_t had_block,
+                                              int32_t act_bits, mquant_stream_t stream)
+{
+    if (act_bits < 2 || act_bits > 8) return MQUANT_ERR_UNSUPPORTED;
     const int st = check_common(x, ldx, T, K, had_block);
     if (st != MQUANT_OK) return st;
     if (n_vis < 0 || n_vis > T) return MQUANT_ERR_BAD_SHAPE;
@@ -365,7 +380,7 @@ extern "C" int mquant_hadamard_quant_act(const void *x, int64_t ldx, const int32
     const float c_vis = static_cast<float>(1.0 / (static_cast<double>(s_vis) * rb));
     const float c_txt = static_cast<float>(1.0 / (static_cast<double>(s_txt) * rb));
     return launch<false>(x, ldx, perm, xq, T, K, n_vis, c_vis, c_txt, had_block, nullptr,
-                         static_cast<hipStream_t>(stream));
+                         static_cast<hipStream_t>(stream), act_bits);
 }
 
 extern "C" int mquant_hadamard_absmax(const void *x, int64_t ldx, int32_t T, int32_t K,

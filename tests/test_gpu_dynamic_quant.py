@@ -116,3 +116,36 @@ def test_dynamic_linear_config1_qkv_sampled(mq):
     assert (xq.cpu().numpy() == want["xq"]).all() and (s.cpu().numpy() == want["s_rows"]).all()
     y = mq.w4a8_gemm_rowscale(xq, mq.w4_prepack(dev(packed)), dev(w_scale), s, N)
     check_y(y.cpu().numpy()[np.ix_(rows, cols)], want["ref"], "c1 qkv dynamic")
+
+
+# ------------------------------------------------ other activation bit-widths
+
+@pytest.mark.parametrize("bits", [4, 6, 8, 2])
+def test_static_quantizer_at_other_bit_widths(mq, bits):
+    """W4A4 and friends: codes bit-exact against the oracle; the GEMM consumes them unchanged."""
+    say(f"static quant bits={bits}")
+    rng = np.random.default_rng(bits)
+    T, K, N, B, V = 70, 1024, 264, 128, 30
+    x = make_x(rng, T, K)
+    u = orc.hadamard_rotate(x, B)
+    s_vis = float(orc.static_scale_from_absmax_bits(np.abs(u[:V]).max(), B, bits))
+    s_txt = float(orc.static_scale_from_absmax_bits(np.abs(u[V:]).max(), B, bits)) * 0.7   # some clipping
+    want = orc.msq_quantize_bits(u, V, s_vis, s_txt, B, bits)
+    xq = mq.hadamard_quant_act(dev(x), V, s_vis, s_txt, B, act_bits=bits)
+    assert (xq.cpu().numpy() == want).all()
+    assert want.min() >= -(1 << (bits - 1)) and want.max() <= (1 << (bits - 1)) - 1
+    packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+    acc_want = orc.gemm_i8_i4_i32(want, orc.unpack_w4(packed))
+    ref, _ = orc.dequant(acc_want, V, s_vis, s_txt, w_scale)
+    acc = torch.empty((T, N), dtype=torch.int32, device="cuda")
+    y = mq.w4a8_gemm(xq, mq.w4_prepack(dev(packed)), dev(w_scale), N, V, s_vis, s_txt, acc_out=acc)
+    assert (acc.cpu().numpy() == acc_want).all()
+    check_y(y.cpu().numpy(), ref, f"bits={bits}")
+
+
+def test_quantizer_rejects_unsupported_bit_width(mq):
+    x = torch.zeros((2, 64), dtype=torch.float16, device="cuda")
+    with pytest.raises(mq.MQuantError) as e:
+        mq.hadamard_quant_act(x, 0, 1.0, 1.0, 64, act_bits=9)
+    assert e.value.status == mq.ERR_UNSUPPORTED
