@@ -597,14 +597,24 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(
 // free: addresses past a wave's K range are clamped and the weights masked to
 // zero, and lanes whose token row is >= T read row T-1 (rows >= T of the MFMA
 // result are never stored).  The partial sums of the waves meet in LDS.
-template <int NWAVES, int KT, int EPI>
+//
+// AROWS > 0 (T <= AROWS): the activations of a batch pass through a wave-private
+// LDS patch.  Read straight from memory, a fragment load touches T rows x 2 pieces of
+// 16 bytes -- at T = 16 four times the cache lines of the 1 KiB weight load next to it;
+// staged, the wave reads each row's 256 bytes of the batch once, 16 lanes per row, and
+// picks the fragments out of LDS (row pitch 272 bytes: conflict free).
+template <int NWAVES, int KT, int EPI, int AROWS>
 __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
     const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
     __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
     int32_t K, Epilogue ep)
 {
     typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-    __shared__ int32_t red[NWAVES][16][64];
+    constexpr int kPatchPitch = KT * 64 + 16;
+    constexpr int kPatchBytes = AROWS * kPatchPitch;
+    constexpr int kWaveBytes = kPatchBytes > 4096 ? kPatchBytes : 4096;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[NWAVES * kWaveBytes];
+    int32_t (*red)[16][64] = reinterpret_cast<int32_t (*)[16][64]>(smem);   // [NWAVES][16][64]
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -628,14 +638,33 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
     const uint4 *wtile = wp + static_cast<int64_t>(ntile) * k_tiles * 64 + lane;
     const int8_t *xrow = xq + static_cast<int64_t>(l32 < T ? l32 : T - 1) * K + g * 32;
 
+    constexpr int NI = AROWS / 4;                         // staging loads per batch: 4 rows each
+    uint8_t *patch = smem + wave * kWaveBytes;
+    const int srow = lane >> 4, scol = lane & 15;
+    const int frag_row = l32 < T ? l32 : T - 1;
+
     for (int32_t base = kt_begin; base < kt_end; base += KT) {
         uint4 a0[KT], a1[KT], b[KT];
+        v4u stage_reg[NI > 0 ? NI : 1];
+        if constexpr (AROWS == 0) {
 #pragma unroll
-        for (int u = 0; u < KT; ++u) {
-            int32_t kt = base + u;
-            kt = kt < kt_end ? kt : kt_end - 1;
-            a0[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64);
-            a1[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64 + 16);
+            for (int u = 0; u < KT; ++u) {
+                int32_t kt = base + u;
+                kt = kt < kt_end ? kt : kt_end - 1;
+                a0[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64);
+                a1[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64 + 16);
+            }
+        } else {
+            // 16 bytes per lane, 16 lanes per row; channels past K are clamped into the row
+            // (their weights are masked to zero below)
+            int32_t kofs = base * 64 + scol * 16;
+            kofs = kofs <= K - 16 ? kofs : K - 16;
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                int32_t r = i * 4 + srow;
+                r = r < T ? r : T - 1;
+                stage_reg[i] = *reinterpret_cast<const v4u *>(xq + static_cast<int64_t>(r) * K + kofs);
+            }
         }
 #pragma unroll
         for (int u = 0; u < KT; ++u) {
@@ -644,6 +673,18 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
             const v4u t = __builtin_nontemporal_load(
                 reinterpret_cast<const v4u *>(wtile + static_cast<int64_t>(kt) * 64));
             b[u] = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+        if constexpr (AROWS > 0) {
+            // same wave writes and reads: LDS operations of a wave complete in order
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+                *reinterpret_cast<v4u *>(patch + (i * 4 + srow) * kPatchPitch + scol * 16) = stage_reg[i];
+#pragma unroll
+            for (int u = 0; u < KT; ++u) {
+                const uint8_t *f = patch + frag_row * kPatchPitch + u * 64 + g * 32;
+                a0[u] = *reinterpret_cast<const uint4 *>(f);
+                a1[u] = *reinterpret_cast<const uint4 *>(f + 16);
+            }
         }
 #pragma unroll
         for (int u = 0; u < KT; ++u) {
@@ -661,9 +702,16 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
         // Scheduling order inside a batch: all 3*KT memory reads first, then the
         // arithmetic.  Without this the scheduler sinks each load next to its use
         // and the wave waits out one memory round trip per k-tile.
-        __builtin_amdgcn_sched_group_barrier(0x020, 3 * KT, 0);
+        if constexpr (AROWS == 0) {
+            __builtin_amdgcn_sched_group_barrier(0x020, 3 * KT, 0);
+        } else {
+            __builtin_amdgcn_sched_group_barrier(0x020, NI + KT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x200, NI, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * KT, 0);
+        }
         __builtin_amdgcn_sched_group_barrier(0x00A, 18 * KT, 0);
     }
+    if constexpr (AROWS > 0) __syncthreads();             // the sums below reuse the patches
 
     // Accumulator register r of k-group g holds row acc_row(r, g): with T <= 8
     // only r < 4 can be a valid row, with T <= 16 only r < 8.
@@ -838,15 +886,27 @@ int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void
             const int8_t *xs = xq + static_cast<int64_t>(t0) * K;
             __half *ys = static_cast<__half *>(y) + static_cast<int64_t>(t0) * ldy;
             int32_t *accs = acc_out ? acc_out + static_cast<int64_t>(t0) * N : nullptr;
-            // Few n-tiles: more waves per tile to keep enough loads in flight.
-            if (n_tiles >= 256)
-                MQ_LAUNCH((w4a8_gemv_kernel<8, 4, EPI>), dim3(n_tiles), dim3(512), 0, stream, xs,
-                          reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
-                          ys, ldy, accs, tt, N, K, slab);
-            else
-                MQ_LAUNCH((w4a8_gemv_kernel<16, 4, EPI>), dim3(n_tiles), dim3(1024), 0, stream, xs,
-                          reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
-                          ys, ldy, accs, tt, N, K, slab);
+            // Few n-tiles: more waves per tile to keep enough loads in flight.  Up to 16 rows:
+            // activations staged through LDS (faster at every T measured, T = 1 included:
+            // a batch then takes 1-4 activation loads instead of 8).
+            const uint4 *wpp = reinterpret_cast<const uint4 *>(wp);
+            const __half *wsc = static_cast<const __half *>(w_scale);
+            const int arows = tt > 16 ? 0 : (tt <= 4 ? 4 : (tt <= 8 ? 8 : 16));
+#define MQ_GEMV(NWV, AR)                                                                        \
+    MQ_LAUNCH((w4a8_gemv_kernel<NWV, 4, EPI, AR>), dim3(n_tiles), dim3(NWV * 64), 0, stream, xs, \
+              wpp, wsc, ys, ldy, accs, tt, N, K, slab)
+            if (n_tiles >= 256) {
+                if (arows == 0) MQ_GEMV(8, 0);
+                else if (arows == 4) MQ_GEMV(8, 4);
+                else if (arows == 8) MQ_GEMV(8, 8);
+                else MQ_GEMV(8, 16);
+            } else {
+                if (arows == 0) MQ_GEMV(16, 0);
+                else if (arows == 4) MQ_GEMV(16, 4);
+                else if (arows == 8) MQ_GEMV(16, 8);
+                else MQ_GEMV(16, 16);
+            }
+#undef MQ_GEMV
             const int ls = launch_status();
             if (ls != MQUANT_OK) return ls;
         }
