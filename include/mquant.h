@@ -317,8 +317,8 @@ int64_t mquant_aifs_attention_workspace_bytes(int32_t T, int32_t n_kv_heads, int
  * three-region rule printed there), evaluated from the positions per tile; no
  * [T, T] mask is read or written.  fp32 softmax statistics, fp16 MFMA operands.
  *   q_dev, k_dev, v_dev, o_dev : as above, leading dimensions in elements
- *                                (ldq, ldk multiples of 8, ldo of 4; q, k 16-byte
- *                                aligned, o 8-byte); o is written
+ *                                (ldq, ldk, ldv multiples of 8, ldo of 4; q, k, v
+ *                                16-byte aligned, o 8-byte); o is written
  *   pos_dev       : int32 [T]; any values (ties attend each other)
  *   workspace_dev : mquant_aifs_attention_workspace_bytes(...) bytes, 256-byte
  *                   aligned; scratch, concurrent calls must not share it

@@ -81,17 +81,28 @@ __global__ __launch_bounds__(256) void vt_kernel(const __half *__restrict__ v, i
                                                  int32_t *__restrict__ tile_min,
                                                  int32_t *__restrict__ tile_max)
 {
-    __shared__ __half tile[64][66];
+    // 64 tokens x 64 channels per group; 16-byte accesses on both sides (channels is a
+    // multiple of 64 here: whole heads of 128).
+    __shared__ __attribute__((aligned(16))) __half tile[64][72];
     const int32_t t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int r = ty; r < 64; r += 4) {
-        const int32_t t = t0 + r, c = c0 + tx;
-        tile[r][tx] = (t < T && c < channels) ? v[static_cast<int64_t>(t) * ldv + c] : __float2half(0.0f);
+    const int r8 = threadIdx.x >> 3, c8 = (threadIdx.x & 7) * 8;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int r = half * 32 + r8;
+        const int32_t t = t0 + r;
+        uint4 val = make_uint4(0u, 0u, 0u, 0u);
+        if (t < T) val = *reinterpret_cast<const uint4 *>(v + static_cast<int64_t>(t) * ldv + c0 + c8);
+        *reinterpret_cast<uint4 *>(&tile[r][c8]) = val;
     }
     __syncthreads();
-    for (int r = ty; r < 64; r += 4) {
-        const int32_t c = c0 + r, t = t0 + tx;
-        if (c < channels && t < Tp) vt[static_cast<int64_t>(c) * Tp + t] = tile[tx][r];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int c = half * 32 + r8;                       // channel row of the transposed tile
+        __half out[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = tile[c8 + i][c];
+        *reinterpret_cast<uint4 *>(vt + static_cast<int64_t>(c0 + c) * Tp + t0 + c8) =
+            *reinterpret_cast<const uint4 *>(out);
     }
     if (blockIdx.y == 0 && threadIdx.x < 64) {
         const int32_t t = t0 + threadIdx.x;
@@ -368,8 +379,8 @@ extern "C" int mquant_aifs_attention(const void *q, int64_t ldq, const void *k, 
     if (!q || !k || !v || !o || !pos) return MQUANT_ERR_NULL;
     const int64_t qw = static_cast<int64_t>(n_q_heads) * head_dim, kw = static_cast<int64_t>(n_kv_heads) * head_dim;
     if (ldq < qw || ldo < qw || ldk < kw || ldv < kw) return MQUANT_ERR_BAD_SHAPE;
-    if (ldq % 8 != 0 || ldk % 8 != 0 || ldo % 4 != 0 || !aligned_to(q, 16) || !aligned_to(k, 16) ||
-        !aligned_to(v, 2) || !aligned_to(o, 8) || !aligned_to(pos, 4))
+    if (ldq % 8 != 0 || ldk % 8 != 0 || ldv % 8 != 0 || ldo % 4 != 0 || !aligned_to(q, 16) ||
+        !aligned_to(k, 16) || !aligned_to(v, 16) || !aligned_to(o, 8) || !aligned_to(pos, 4))
         return MQUANT_ERR_ALIGNMENT;
     const int64_t need = mquant_aifs_attention_workspace_bytes(T, n_kv_heads, head_dim);
     if (!workspace || workspace_bytes < need) return MQUANT_ERR_WORKSPACE;
