@@ -121,6 +121,18 @@ def test_attention_config2_layout_sampled(mq):
     check_attention(mq, q[perm], k[perm], v[perm], perm, Hq, Hkv, rows=rows, what="c2")
 
 
+def test_attention_config1_layout_sampled(mq):
+    """configs[1]: T = 1280 (visual 16..1039), 28 query heads on 4 key/value heads, the launch
+    bench.py times; sampled rows."""
+    say("attention c1 sampled")
+    rng = np.random.default_rng(7)
+    T, Hq, Hkv = 1280, 28, 4
+    q, k, v = make_qkv(rng, T, Hq, Hkv, q_gain=0.3)
+    perm, _, V = orc.aifs_build_perm(T, [(16, 1024)])
+    rows = np.unique(np.r_[0, 1, 127, 128, V - 1, V, V + 15, V + 16, T - 1, rng.choice(T, 24, replace=False)])
+    check_attention(mq, q[perm], k[perm], v[perm], perm, Hq, Hkv, rows=rows, what="c1")
+
+
 def test_attention_argument_errors(mq):
     x = torch.zeros((4, 128), dtype=torch.float16, device="cuda")
     pos = torch.zeros(4, dtype=torch.int32, device="cuda")

@@ -139,3 +139,30 @@ def test_rms_end_to_end_from_float_weights(mq):
     y0 = mq.w4a8_gemm(xq, mq.w4_prepack(dev(pack_int4(wq0))), dev(s0), N, 0, s_act, s_act).cpu().numpy()
     want = x.astype(np.float64) @ W
     assert np.abs(y - want).mean() < 0.6 * np.abs(y0 - want).mean()
+
+
+@pytest.mark.parametrize("n_split", [1, 37])
+def test_rms_full_size_down_projection_sampled(mq, n_split):
+    """configs[1] down projection (1280 x 18944 x 3584, the split-K launch bench.py times) with
+    one flagged channel and with one per Hadamard block; sampled rows x channels."""
+    say(f"rms full-size down splits={n_split}")
+    rng = np.random.default_rng(100 + n_split)
+    T, K, N, B = 1280, 18944, 3584, 512
+    xq, wq, idx, wsplit, ssplit, w_scale = make_case(rng, T, N, K, B, n_split)
+    V, s_vis, s_txt = 1024, 0.11, 0.004
+    rows = np.unique(np.r_[0, 1, 255, 256, V - 1, V, T - 1, rng.choice(T, 24, replace=False)])
+    cols = np.unique(np.r_[0, 1, 31, 32, 255, 256, N - 1, rng.choice(N, 96, replace=False)])
+    acc_want = orc.gemm_i8_i4_i32(xq[rows], wq[cols])
+    ref = np.empty(acc_want.shape, dtype=np.float32)
+    main = np.empty_like(ref)
+    for sel, v_count in ((rows < V, None), (rows >= V, 0)):
+        if not sel.any():
+            continue
+        vv = int(sel.sum()) if v_count is None else 0
+        ref[sel], _ = orc.dequant_rms(acc_want[sel], xq[rows][sel], vv, s_vis, s_txt, w_scale[cols], idx,
+                                      wsplit[:, cols], ssplit)
+        main[sel], _ = orc.dequant(acc_want[sel], vv, s_vis, s_txt, w_scale[cols])
+    mag = np.abs(main) + np.abs(ref - main)
+    y = mq.w4a8_gemm_rms(dev(xq), mq.w4_prepack(dev(pack_int4(wq))), dev(w_scale), N, V, s_vis, s_txt,
+                         idx, dev(wsplit), ssplit)
+    check(y.cpu().numpy()[np.ix_(rows, cols)], ref, mag, f"full-size down, {n_split} split channels")
