@@ -140,9 +140,9 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
     const int32_t *__restrict__ pos, const int32_t *__restrict__ tile_min,
     const int32_t *__restrict__ tile_max, int32_t T, int32_t group, float scale_log2e)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t k_lds[kBK * kKPitch];
-    __shared__ __attribute__((aligned(16))) uint8_t v_lds[kHeadDim * kVPitch];
-    __shared__ int32_t pos_lds[kBK];
+    __shared__ __attribute__((aligned(16))) uint8_t k_lds2[2][kBK * kKPitch];
+    __shared__ __attribute__((aligned(16))) uint8_t v_lds2[2][kHeadDim * kVPitch];
+    __shared__ int32_t pos_lds2[2][kBK];
     __shared__ int32_t wg_qmax_lds[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -177,7 +177,6 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[dt][r] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
 
     // ---- tile staging through registers: 4 chunks of K and 4 of V^T per thread
     v4u kreg[4];                                           // native vectors: HIP's uint4 struct
@@ -204,32 +203,48 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
             preg = key < T ? pos[key] : INT_MAX;
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](int b) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int c = tid + 256 * i, row = c >> 4, col = c & 15;
-            *reinterpret_cast<v4u *>(k_lds + row * kKPitch + col * 16) = kreg[i];
+            *reinterpret_cast<v4u *>(k_lds2[b] + row * kKPitch + col * 16) = kreg[i];
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int c = tid + 256 * i, d = c >> 4, col = c & 15;
-            *reinterpret_cast<v2u *>(v_lds + d * kVPitch + col * 8) = vreg[i];
+            *reinterpret_cast<v2u *>(v_lds2[b] + d * kVPitch + col * 8) = vreg[i];
         }
-        if (tid < kBK) pos_lds[tid] = preg;
+        if (tid < kBK) pos_lds2[b][tid] = preg;
     };
     auto next_tile = [&](int32_t t) {                     // first tile >= t the group needs, or n_tiles
         while (t < n_tiles && tile_min[t] > wg_qmax) ++t;
         return t;
     };
 
+    // Running statistics in raw-logit units; the exponent is exp2((s - m_ref) * c) as one
+    // fused multiply-add per element.  m_ref is the reference maximum the accumulators are
+    // scaled to; it follows the true maximum lazily: only when some query's maximum has grown
+    // by more than kLazy (a factor 2^kLazy in the probabilities, harmless in fp16 and fp32)
+    // are the accumulators rescaled, so most tiles skip the 64 multiplies and the exponential.
+    constexpr float kLazy = 8.0f;
+    const float lazy_raw = kLazy / scale_log2e;
+    float m_ref = -INFINITY, l_run = 0.0f;
+
     int32_t t = next_tile(0);                              // tile of the group's own positions at the latest
     fetch(t < n_tiles ? t : 0);
+    stage(0);
+    int32_t tn = next_tile(t + 1);
+    fetch(tn < n_tiles ? tn : (t < n_tiles ? t : 0));      // unconditional: a harmless re-read at the end
+    __syncthreads();
+    int buf = 0;
     while (t < n_tiles) {
-        __syncthreads();                                   // every wave is done with the previous tile
-        stage();
-        __syncthreads();
-        const int32_t tn = next_tile(t + 1);
-        fetch(tn < n_tiles ? tn : t);                      // unconditional: the last one is a harmless re-read
+        // Registers hold tile tn: into the other buffer, which every wave left at the barrier
+        // that ended the previous iteration.  Then request the tile after it.
+        stage(buf ^ 1);
+        const int32_t tnn = tn < n_tiles ? next_tile(tn + 1) : n_tiles;
+        fetch(tnn < n_tiles ? tnn : t);
+        const uint8_t *k_lds = k_lds2[buf], *v_lds = v_lds2[buf];
+        const int32_t *pos_lds = pos_lds2[buf];
 
         const int32_t kmin = tile_min[t], kmax = tile_max[t];
         const bool padded = (t + 1) * kBK > T;             // tile holds keys past the end
@@ -249,48 +264,44 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
                         k_lds + (kb * 32 + l32) * kKPitch + g * 16 + ks * 32);
                     s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qf[ks], s[kb], 0, 0, 0);
                 }
-            // ---- scale (base-2 logits), mask, online softmax
-            const bool need_mask = kmax > qmin || padded;
-            float m_new = m_run;
-            if (need_mask) {                               // wave-uniform
+            // ---- mask, online softmax
+            if (kmax > qmin || padded) {                   // wave-uniform: some (query, key) pair is hidden
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const bool hidden = pos_lds[kb * 32 + acc_row(r, g)] > my_pos;
-                        s[kb][r] = hidden ? -INFINITY : s[kb][r] * scale_log2e;
-                    }
-            } else {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) s[kb][r] *= scale_log2e;
+                    for (int r = 0; r < 16; ++r)
+                        if (pos_lds[kb * 32 + acc_row(r, g)] > my_pos) s[kb][r] = -INFINITY;
             }
+            float m_new = m_ref;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) m_new = fmaxf(m_new, s[kb][r]);
             m_new = fmaxf(m_new, __shfl_xor(m_new, 32, 64));     // the query's other 32 keys
-            const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // 0 while nothing was visible
+            if (__any(m_new > m_ref + lazy_raw)) {         // also the first visible tile (m_ref = -inf)
+                const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+                const float alpha = __builtin_amdgcn_exp2f((m_ref - m_use) * scale_log2e);   // exp2(-inf) = 0
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha;
+                m_ref = m_new;
+            }
+            const float neg = m_ref == -INFINITY ? 0.0f : -m_ref * scale_log2e;
             float l_add = 0.0f;
             v8h p[4];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float e = __builtin_amdgcn_exp2f(s[kb][r] - m_use);    // exp2(-inf) = 0
+                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], scale_log2e, neg));
                     l_add += e;
                     p[kb * 2 + (r >> 3)][r & 7] = static_cast<_Float16>(e);
                 }
             l_add += __shfl_xor(l_add, 32, 64);
-            l_run = l_run * alpha + l_add;
-            m_run = m_new;
-            // ---- O^T = O^T * alpha + V^T P^T (the four channel blocks alternate)
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc_o[dt][r] *= alpha;
+            l_run += l_add;
+            // ---- O^T += V^T P^T (the four channel blocks alternate)
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
@@ -308,7 +319,10 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
                     acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p[kk], acc_o[dt], 0, 0, 0);
                 }
         }
+        __syncthreads();                                   // buffer buf is free, buffer buf^1 is published
         t = tn;
+        tn = tnn;
+        buf ^= 1;
     }
 
     // ---- normalise and store: lane = query, registers = head channels (4 consecutive per group)
