@@ -149,3 +149,23 @@ def test_quantizer_rejects_unsupported_bit_width(mq):
     with pytest.raises(mq.MQuantError) as e:
         mq.hadamard_quant_act(x, 0, 1.0, 1.0, 64, act_bits=9)
     assert e.value.status == mq.ERR_UNSUPPORTED
+
+
+def test_empty_inputs_of_the_widened_entry_points(mq):
+    """T = 0 is a valid no-op everywhere."""
+    e16 = torch.empty((0, 512), dtype=torch.float16, device="cuda")
+    xq, s = mq.hadamard_dynquant_act(e16, 512)
+    assert xq.shape == (0, 512) and s.shape == (0,)
+    wp = mq.w4_prepack(dev(np.zeros((32, 256), dtype=np.uint8)))
+    ws = dev(np.ones(32, dtype=np.float16))
+    y = mq.w4a8_gemm_rowscale(torch.empty((0, 512), dtype=torch.int8, device="cuda"), wp, ws,
+                              torch.empty(0, dtype=torch.float32, device="cuda"), 32)
+    assert y.shape == (0, 32)
+    y = mq.w4a8_gemm_rms(torch.empty((0, 512), dtype=torch.int8, device="cuda"), wp, ws, 32, 0, 1.0, 1.0,
+                         np.zeros(1, np.int32), dev(np.zeros((1, 32), np.int8)), np.ones(1, np.float32))
+    assert y.shape == (0, 32)
+    q = torch.empty((0, 128), dtype=torch.float16, device="cuda")
+    pos = torch.empty(0, dtype=torch.int32, device="cuda")
+    assert mq.aifs_attention(q, q, q, pos, 1, 1).shape == (0, 128)
+    mq.rope_apply(q, pos, 1)
+    torch.cuda.synchronize()
