@@ -45,6 +45,7 @@ def parse_args():
     ap.add_argument("--decode-layers", type=int, default=28)
     ap.add_argument("--decode-iters", type=int, default=10)
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the attainable-peak probes")
     ap.add_argument("--no-attention", action="store_true", help="skip the attention / RoPE leg")
     ap.add_argument("--no-rms", action="store_true", help="skip the RMS split-path leg")
     ap.add_argument("--no-dynamic", action="store_true", help="skip the per-token dynamic baseline leg")
@@ -222,6 +223,41 @@ def main():
                       "GBps": round(fe_bytes / (fe_ms * 1e-3) / 1e9, 1),
                       "frac": round(fe_bytes / (fe_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
     }
+
+    # ------------------------------------------------- attainable peaks, measured live
+    # What this machine reaches on the two bounding resources: an MFMA-only int8 loop on random
+    # operands (the matrix clock drops under data-dependent power; zeros for comparison) and a
+    # read-only stream over 2 GiB.  The published peaks stay the denominators of `frac`.
+    if not args.no_probes:
+        def timed_once(fn, reps=3):
+            fn()
+            torch.cuda.synchronize()
+            best = float("inf")
+            for _ in range(reps):
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn()
+                e1.record()
+                e1.synchronize()
+                best = min(best, e0.elapsed_time(e1))
+            return best
+        gen_p = torch.Generator(device="cuda")
+        gen_p.manual_seed(5000)
+        rnd = torch.randint(0, 256, (1 << 16,), dtype=torch.uint8, device="cuda", generator=gen_p)
+        zer = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        iters = 20000
+        ops = float(mq.probe_mfma_i8(iters, rnd, sink))
+        att = {"mfma_i8_random_operands_TOPS": round(ops / timed_once(lambda: mq.probe_mfma_i8(iters, rnd, sink)) / 1e9, 1),
+               "mfma_i8_zero_operands_TOPS": round(ops / timed_once(lambda: mq.probe_mfma_i8(iters, zer, sink)) / 1e9, 1)}
+        big = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+        nbytes = float(mq.probe_hbm_read(big, sink))
+        att["hbm_read_GBps"] = round(nbytes / timed_once(lambda: mq.probe_hbm_read(big, sink)) / 1e6, 1)
+        del big
+        torch.cuda.empty_cache()
+        result["attainable"] = att
+        result["roofline"]["frac_of_attainable"] = round(gemm_tops / att["mfma_i8_random_operands_TOPS"], 4)
 
     # ------------------------------------------- per-token dynamic baseline (context)
     # The scheme the paper's speed tables compare against: same rotation, same GEMM, but

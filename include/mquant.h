@@ -332,6 +332,29 @@ int mquant_aifs_attention(const void *q_dev, int64_t ldq, const void *k_dev, int
                           int32_t head_dim, void *workspace_dev, int64_t workspace_bytes,
                           mquant_stream_t stream);
 
+/* -------------------------------------------------------------------------
+ * Measurement probes.  Not part of the method: they measure what this chip
+ * attains on the two resources the path is bound by (for the benchmark's
+ * "attainable" figures).  Both are DEVICE calls, asynchronous like the rest.
+ * ---------------------------------------------------------------------- */
+
+/* int8 operations one mquant_probe_mfma_i8(iters) launch performs. */
+int64_t mquant_probe_mfma_i8_ops(int32_t iters);
+
+/*
+ * An MFMA-only loop (v_mfma_i32_32x32x32_i8, eight independent accumulators
+ * per wave, four waves per SIMD on every CU) whose operands are read once from
+ * data_dev (>= 4096 bytes, 16-byte aligned; its contents set the data-dependent
+ * matrix clock: zeros, or random bytes as in a real product).  sink_dev: one
+ * int32 that is practically never written.
+ */
+int mquant_probe_mfma_i8(int32_t iters, const void *data_dev, int64_t data_bytes, int32_t *sink_dev,
+                         mquant_stream_t stream);
+
+/* A read-only stream over data_bytes of data_dev (16-byte aligned), 16 bytes per lane. */
+int mquant_probe_hbm_read(const void *data_dev, int64_t data_bytes, uint32_t *sink_dev,
+                          mquant_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

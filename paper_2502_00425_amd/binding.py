@@ -30,6 +30,7 @@ EXPORTS = (
     "mquant_hadamard_dynquant_act", "mquant_w4a8_gemm_rowscale", "mquant_w4a8_gemm_rms",
     "mquant_rope_apply", "mquant_aifs_attention_workspace_bytes", "mquant_aifs_attention",
     "mquant_hadamard_quant_act_bits",
+    "mquant_probe_mfma_i8_ops", "mquant_probe_mfma_i8", "mquant_probe_hbm_read",
 )
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGNMENT = 0, -1, -2, -3, -4, -5, -6
@@ -79,8 +80,13 @@ def _load() -> ctypes.CDLL:
     lib.mquant_aifs_attention_workspace_bytes.restype = i64
     lib.mquant_aifs_attention_workspace_bytes.argtypes = [i32, i32, i32]
     lib.mquant_aifs_attention.argtypes = [p, i64, p, i64, p, i64, p, i64, p, i32, i32, i32, i32, p, i64, p]
+    lib.mquant_probe_mfma_i8_ops.restype = i64
+    lib.mquant_probe_mfma_i8_ops.argtypes = [i32]
+    lib.mquant_probe_mfma_i8.argtypes = [i32, p, i64, p, p]
+    lib.mquant_probe_hbm_read.argtypes = [p, i64, p, p]
     for name in EXPORTS:
         if name not in ("mquant_status_string", "mquant_w4_prepacked_bytes", "mquant_aifs_attention_workspace_bytes",
+                        "mquant_probe_mfma_i8_ops",
                         "mquant_w4a8_workspace_bytes", "mquant_w4a8_linear_prefill_workspace_bytes",
                         "mquant_version"):
             getattr(lib, name).restype = ctypes.c_int
@@ -329,3 +335,17 @@ def aifs_attention(q, k, v, pos_dev, n_q_heads: int, n_kv_heads: int, head_dim: 
                                      head_dim, _dp(workspace), ws_bytes, _stream()),
            "mquant_aifs_attention")
     return out
+
+
+def probe_mfma_i8(iters: int, data, sink) -> int:
+    """Launches the MFMA-only loop; returns the int8 operations it performs."""
+    _check(lib.mquant_probe_mfma_i8(iters, _dp(data), data.numel() * data.element_size(), _dp(sink),
+                                    _stream()), "mquant_probe_mfma_i8")
+    return int(lib.mquant_probe_mfma_i8_ops(iters))
+
+
+def probe_hbm_read(data, sink) -> int:
+    """Launches the read-only stream; returns the bytes it reads."""
+    n = data.numel() * data.element_size()
+    _check(lib.mquant_probe_hbm_read(_dp(data), n, _dp(sink), _stream()), "mquant_probe_hbm_read")
+    return n

@@ -410,3 +410,14 @@ def test_config3_decode_full(mq, T):
 @pytest.mark.parametrize("proj", ["qkv", "o", "gate_up", "down"])
 def test_config4_72b_T16384(mq, proj):
     full_size_case(mq, 4, proj, fused=(proj in ("gate_up", "down")))
+
+
+def test_measurement_probes_run(mq):
+    """The attainable-peak probes of the benchmark: launch, finish, report their work."""
+    data = torch.randint(0, 256, (1 << 16,), dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    assert mq.probe_mfma_i8(10, data, sink) == 10 * 8 * 65536 * 4 * 1024
+    assert mq.probe_hbm_read(data, sink) == 1 << 16
+    torch.cuda.synchronize()
+    assert mq.lib.mquant_probe_mfma_i8(-1, data.data_ptr(), 1 << 16, sink.data_ptr(), None) == mq.ERR_BAD_SHAPE
+    assert mq.lib.mquant_probe_hbm_read(None, 16, sink.data_ptr(), None) == mq.ERR_NULL
