@@ -427,6 +427,11 @@ def bench_attention(args, torch, mq, wl, np):
             return best
 
         ms = timed(lambda: mq.aifs_attention(q, k, v, pos, Hq, Hkv, out=o, workspace=ws))
+        # the same kernel on tokens in their original order (positions 0..T-1: a plain causal
+        # mask): what the reorder costs the attention (the paper's comparison of FlashAttention
+        # with and without AIFS)
+        pos_plain = torch.arange(T, dtype=torch.int32, device="cuda")
+        ms_plain = timed(lambda: mq.aifs_attention(q, k, v, pos_plain, Hq, Hkv, out=o, workspace=ws))
         pairs = T * (T + 1) // 2                      # allowed pairs of a causal mask in any order
         flops = 4.0 * D * pairs * Hq
         ms_rope = timed(lambda: mq.rope_apply(qkv[:, :(Hq + Hkv) * D], pos, Hq + Hkv))
@@ -434,6 +439,8 @@ def bench_attention(args, torch, mq, wl, np):
         out["per_config"]["configs[%d] T=%d" % (cfg, T)] = {
             "attention_us": round(ms * 1e3, 1), "TFLOPs": round(flops / ms / 1e9, 1),
             "frac": round(flops / ms / 1e9 / 2500.0, 4),
+            "plain_causal_order_us": round(ms_plain * 1e3, 1),
+            "aifs_overhead": round(ms / ms_plain - 1.0, 4),
             "rope_us": round(ms_rope * 1e3, 2), "rope_GBps": round(rope_bytes / ms_rope / 1e6, 1)}
     return out
 
