@@ -492,6 +492,12 @@ def bench_decode(args, torch, mq, wl):
                     mq.hadamard_quant_act(xs[K], 0, s_txt, s_txt, 512, out=xq[K])
                     mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
 
+        def fused_linear_pass():
+            # front end inside the GEMV launch (T <= 4): one launch per linear
+            for layer in layers:
+                for proj, (K, N, wp, ws) in layer.items():
+                    mq.w4a8_linear_decode(xs[K], wp, ws, N, 0, s_txt, s_txt, 512, out=ys[N])
+
         def gemv_only_pass():
             for layer in layers:
                 for proj, (K, N, wp, ws) in layer.items():
@@ -521,9 +527,12 @@ def bench_decode(args, torch, mq, wl):
 
         bytes_layer = sum(K * N / 2 + 2 * N + T * K + 2 * T * N for (K, N) in wd.projections.values())
         res = {}
-        for name, fn in (("quant+gemv", one_pass), ("gemv_only", gemv_only_pass),
+        legs = [("quant+gemv", one_pass)]
+        if T <= 4:
+            legs.append(("quant+gemv_one_launch", fused_linear_pass))
+        for name, fn in legs + [("gemv_only", gemv_only_pass),
                          ("gemv_only_fused_qkv_gateup", gemv_fused_pass),
-                         ("gemv_only_4streams", gemv_streams_pass)):
+                         ("gemv_only_4streams", gemv_streams_pass)]:
             fn()
             torch.cuda.synchronize()
             if args.no_graphs:

@@ -286,6 +286,23 @@ int mquant_w4a8_linear_prefill(const void *x_dev, int64_t ldx, const int32_t *pe
                                void *workspace_dev, int64_t workspace_bytes,
                                mquant_stream_t stream);
 
+/*
+ * DEVICE.  The whole path of one linear at decode (T <= 4 new rows) in ONE
+ * launch: block-Hadamard rotation and static quantization of x (as
+ * mquant_hadamard_quant_act, no gather) inside the weight-streaming GEMV, then
+ * the fused dequantisation.  Equivalent to mquant_hadamard_quant_act followed by
+ * mquant_w4a8_gemm, bit for bit; saves the separate front-end launch, which at
+ * decode costs about as much as a small GEMV.
+ *   x_dev : fp16 [T, K], leading dimension ldx (multiple of 8), 16-byte aligned
+ *   had_block : 1, 128 or 512 (ERR_UNSUPPORTED otherwise, also for T > 4 and for
+ *               T * (K + 16) > 150 KiB, the LDS copy of the quantized rows)
+ * Other arguments and errors as in mquant_w4a8_gemm; no workspace.
+ */
+int mquant_w4a8_linear_decode(const void *x_dev, int64_t ldx, const uint8_t *w_prepacked_dev,
+                              const void *w_scale_dev, void *y_dev, int64_t ldy, int32_t T, int32_t N,
+                              int32_t K, int32_t n_vis, float s_vis, float s_txt, int32_t had_block,
+                              mquant_stream_t stream);
+
 /* -------------------------------------------------------------------------
  * Attention on AIFS-ordered tokens (Sec. 3.1, Eq. (5)-(6)) and rotary position
  * embedding with the reordered position ids (appendix "Rotary Position

@@ -31,6 +31,7 @@ EXPORTS = (
     "mquant_rope_apply", "mquant_aifs_attention_workspace_bytes", "mquant_aifs_attention",
     "mquant_hadamard_quant_act_bits",
     "mquant_probe_mfma_i8_ops", "mquant_probe_mfma_i8", "mquant_probe_hbm_read",
+    "mquant_w4a8_linear_decode",
 )
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGNMENT = 0, -1, -2, -3, -4, -5, -6
@@ -80,6 +81,7 @@ def _load() -> ctypes.CDLL:
     lib.mquant_aifs_attention_workspace_bytes.restype = i64
     lib.mquant_aifs_attention_workspace_bytes.argtypes = [i32, i32, i32]
     lib.mquant_aifs_attention.argtypes = [p, i64, p, i64, p, i64, p, i64, p, i32, i32, i32, i32, p, i64, p]
+    lib.mquant_w4a8_linear_decode.argtypes = [p, i64, p, p, p, i64, i32, i32, i32, i32, f32, f32, i32, p]
     lib.mquant_probe_mfma_i8_ops.restype = i64
     lib.mquant_probe_mfma_i8_ops.argtypes = [i32]
     lib.mquant_probe_mfma_i8.argtypes = [i32, p, i64, p, p]
@@ -349,3 +351,16 @@ def probe_hbm_read(data, sink) -> int:
     n = data.numel() * data.element_size()
     _check(lib.mquant_probe_hbm_read(_dp(data), n, _dp(sink), _stream()), "mquant_probe_hbm_read")
     return n
+
+
+def w4a8_linear_decode(x, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float, s_txt: float,
+                       had_block: int, out=None):
+    """x fp16 [T <= 4, K] -> y fp16 [T, N]: rotate, quantize, GEMV and dequant in one launch."""
+    import torch
+    T, K = x.shape
+    if out is None:
+        out = torch.empty((T, N), dtype=torch.float16, device=x.device)
+    _check(lib.mquant_w4a8_linear_decode(_dp(x), x.stride(0), _dp(w_prepacked), _dp(w_scale), _dp(out),
+                                         out.stride(0), T, N, K, n_vis, s_vis, s_txt, had_block,
+                                         _stream()), "mquant_w4a8_linear_decode")
+    return out

@@ -31,7 +31,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "mquant_internal.h"),
+    deps = sources() + [os.path.join(CSRC, "mquant_internal.h"), os.path.join(CSRC, "hadamard_segment.h"),
                         os.path.join(ROOT, "include", "mquant.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 

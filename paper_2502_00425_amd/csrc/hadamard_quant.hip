@@ -11,213 +11,12 @@
 #include <hip/hip_fp16.h>
 #include <math.h>
 
+#include "hadamard_segment.h"
 #include "mquant_internal.h"
 
 using namespace mquant;
 
 namespace {
-
-template <int B>
-__device__ __forceinline__ void register_stages(float (&v)[8])
-{
-    // h = 1, 2, 4 inside the lane's eight contiguous channels.
-#pragma unroll
-    for (int h = 1; h < 8 && h < B; h <<= 1) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if ((j & h) == 0) {
-                const float a = v[j], b = v[j + h];
-                v[j] = a + b;
-                v[j + h] = a - b;
-            }
-        }
-    }
-}
-
-// Value of lane (l ^ M) for M in {1, 2, 4, 8, 16, 32}, without touching LDS
-// memory: DPP quad/row permutes inside a row of 16 lanes, a swizzle across the
-// two rows of a half-wave, the half-wave swap instruction across the halves.
-template <int M>
-__device__ __forceinline__ float lane_xor(float x, int lane)
-{
-    const int xi = __float_as_int(x);
-    int r;
-    if constexpr (M == 1) {
-        r = __builtin_amdgcn_update_dpp(0, xi, 0xB1, 0xF, 0xF, true);       // quad_perm [1,0,3,2]
-    } else if constexpr (M == 2) {
-        r = __builtin_amdgcn_update_dpp(0, xi, 0x4E, 0xF, 0xF, true);       // quad_perm [2,3,0,1]
-    } else if constexpr (M == 4) {
-        // i -> 7 - i inside each group of 8, then reverse inside each quad: i -> i ^ 4
-        const int t = __builtin_amdgcn_update_dpp(0, xi, 0x141, 0xF, 0xF, true);   // row_half_mirror
-        r = __builtin_amdgcn_update_dpp(0, t, 0x1B, 0xF, 0xF, true);               // quad_perm [3,2,1,0]
-    } else if constexpr (M == 8) {
-        r = __builtin_amdgcn_update_dpp(0, xi, 0x128, 0xF, 0xF, true);      // row_ror:8
-    } else if constexpr (M == 16) {
-        r = __builtin_amdgcn_ds_swizzle(xi, 0x401F);                        // bit mode, xor 16
-    } else {
-        static_assert(M == 32, "lane_xor distance");
-        // {x[0..31], x[0..31]} and {x[32..63], x[32..63]}
-        const auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
-        r = lane < 32 ? sw[1] : sw[0];
-    }
-    return __int_as_float(r);
-}
-
-template <int B, int M>
-__device__ __forceinline__ void lane_stage(float (&v)[8], int lane)
-{
-    if constexpr (8 * M < B) {
-        if constexpr (M < 16) {
-            // The lane holding the lower index keeps a + b, the other one a - b with
-            // a the lower-index value: other + (upper ? -mine : mine), one add each.
-            const int sign = (lane & M) ? static_cast<int>(0x80000000u) : 0;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float other = lane_xor<M>(v[j], lane);
-                const float mine = __int_as_float(__float_as_int(v[j]) ^ sign);
-                v[j] = other + mine;
-            }
-        } else {
-            // Partner lanes sit in different rows (M = 16) or wave halves (M = 32).
-            // The row / half swap instructions exchange the odd rows (upper half)
-            // of one register with the even rows (lower half) of another: applied to
-            // (v[j], v[j+4]) it leaves every lane with a complete pair (a, b) -- the
-            // lower-index lanes for register j, the upper-index lanes for j+4 --
-            // so each lane does one add and one subtract, and the same swap puts the
-            // results back where they belong.  No select, no LDS.
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int lo = __float_as_int(v[j]), hi = __float_as_int(v[j + 4]);
-                float a, b;
-                if constexpr (M == 16) {
-                    const auto sw = __builtin_amdgcn_permlane16_swap(lo, hi, false, false);
-                    a = __int_as_float(sw[0]);
-                    b = __int_as_float(sw[1]);
-                } else {
-                    const auto sw = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
-                    a = __int_as_float(sw[0]);
-                    b = __int_as_float(sw[1]);
-                }
-                const int p = __float_as_int(a + b), q = __float_as_int(a - b);
-                if constexpr (M == 16) {
-                    const auto sw = __builtin_amdgcn_permlane16_swap(p, q, false, false);
-                    v[j] = __int_as_float(sw[0]);
-                    v[j + 4] = __int_as_float(sw[1]);
-                } else {
-                    const auto sw = __builtin_amdgcn_permlane32_swap(p, q, false, false);
-                    v[j] = __int_as_float(sw[0]);
-                    v[j + 4] = __int_as_float(sw[1]);
-                }
-            }
-        }
-    }
-}
-
-template <int B>
-__device__ __forceinline__ void lane_stages(float (&v)[8], int lane)
-{
-    // h = 8, 16, ..., min(B, 512)/2: partner lane differs in bit h/8.
-    lane_stage<B, 1>(v, lane);
-    lane_stage<B, 2>(v, lane);
-    lane_stage<B, 4>(v, lane);
-    lane_stage<B, 8>(v, lane);
-    lane_stage<B, 16>(v, lane);
-    lane_stage<B, 32>(v, lane);
-}
-
-// One wave segment: SEG = max(B, 512) consecutive channels of one row, C = SEG/512
-// chunks of 512, 8 channels per lane and chunk.  Loads fp16, rotates in fp32.
-template <int B>
-struct Segment {
-    static constexpr int C = B > 512 ? B / 512 : 1;
-    static constexpr int SEG = 512 * C;
-    float v[C][8];
-    bool valid[C];
-
-    __device__ __forceinline__ void load_rotate(const __half *row, int32_t sidx, int32_t K, int lane)
-    {
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            const int32_t k0 = sidx * SEG + c * 512 + lane * 8;
-            valid[c] = k0 < K;
-            if (valid[c]) {
-                const uint4 raw = *reinterpret_cast<const uint4 *>(row + k0);
-                const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float2 f = __half22float2(h2[j]);
-                    v[c][2 * j] = f.x;
-                    v[c][2 * j + 1] = f.y;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) v[c][j] = 0.0f;
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            register_stages<B>(v[c]);
-            lane_stages<B>(v[c], lane);
-        }
-        // h = 512, ...: across the wave segment's chunks.
-#pragma unroll
-        for (int hc = 1; hc < C; hc <<= 1) {
-#pragma unroll
-            for (int c = 0; c < C; ++c) {
-                if ((c & hc) == 0) {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const float a = v[c][j], b = v[c + hc][j];
-                        v[c][j] = a + b;
-                        v[c + hc][j] = a - b;
-                    }
-                }
-            }
-        }
-    }
-
-    __device__ __forceinline__ float absmax(float m) const
-    {
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            if (valid[c]) {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(v[c][j]));
-            }
-        }
-        return m;
-    }
-
-    // int8 codes clamp(rne(v * cmul)) of this segment into row `xq_row`.
-    __device__ __forceinline__ void quant_store(float cmul, int8_t *xq_row, int32_t sidx, int lane,
-                                                float q_lo = -128.0f, float q_hi = 127.0f) const
-    {
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            if (valid[c]) {
-                // clamp(rint(t)) == rint(clamp(t)) for integer bounds; adding 1.5 * 2^23
-                // rounds to an integer (ties to even) and leaves it in the low mantissa
-                // bits, whose low byte is the two's-complement int8 code.
-                uint32_t bits[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float t = __builtin_amdgcn_fmed3f(v[c][j] * cmul, q_lo, q_hi);
-                    bits[j] = __float_as_uint(t + 12582912.0f);
-                }
-                uint32_t packed[2];
-#pragma unroll
-                for (int w = 0; w < 2; ++w) {
-                    // byte 0 of four words -> one dword
-                    const uint32_t p01 = __builtin_amdgcn_perm(bits[4 * w + 1], bits[4 * w], 0x0c0c0400u);
-                    const uint32_t p23 = __builtin_amdgcn_perm(bits[4 * w + 3], bits[4 * w + 2], 0x04000c0cu);
-                    packed[w] = p01 | p23;
-                }
-                const int64_t k0 = static_cast<int64_t>(sidx) * SEG + c * 512 + lane * 8;
-                *reinterpret_cast<uint2 *>(xq_row + k0) = make_uint2(packed[0], packed[1]);
-            }
-        }
-    }
-};
 
 template <int B, bool ABSMAX>
 __global__ __launch_bounds__(256) void hadamard_quant_kernel(

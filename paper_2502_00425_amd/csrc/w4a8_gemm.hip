@@ -25,6 +25,7 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include "hadamard_segment.h"
 #include "mquant_internal.h"
 
 using namespace mquant;
@@ -733,6 +734,127 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
     }
 }
 
+// Decode with the front end fused in (T <= 4): every work-group first rotates and
+// quantizes the T input rows itself (Sec. 3.2 rotation, Eq. (2)/(3) static
+// quantizer: the same wave-level code as the stand-alone kernel, one 512-channel
+// segment per wave at a time) into an LDS copy of xq, then streams its weight tile
+// as above with the activation fragments read from that copy.  The rotation is
+// redundant across work-groups but costs a few hundred cycles per wave against a
+// separate launch per linear (about 2 us each in a 7-linear decoder layer).
+template <int NWAVES, int KT, int B>
+__global__ __launch_bounds__(NWAVES * 64) void w4a8_decode_fused_kernel(
+    const __half *__restrict__ x, int64_t ldx, const uint4 *__restrict__ wp,
+    const __half *__restrict__ w_scale, __half *__restrict__ y, int64_t ldy, int32_t T, int32_t N,
+    int32_t K, Epilogue ep, float c_vis, float c_txt)
+{
+    typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];     // max(T * pitch, NWAVES * 4096)
+    int32_t (*red)[16][64] = reinterpret_cast<int32_t (*)[16][64]>(smem);
+    const int32_t pitch = K + 16;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    const int g = lane >> 5;
+    const int32_t ntile = blockIdx.x;
+    const int32_t k_tiles = K / kPackK;
+    const int32_t per_wave = (k_tiles + NWAVES - 1) / NWAVES;
+    const int32_t kt_begin = wave * per_wave;
+    int32_t kt_end = kt_begin + per_wave;
+    kt_end = kt_end < k_tiles ? kt_end : k_tiles;
+    const int32_t n = ntile * 32 + l32;
+    const __half ws_h = w_scale[n < N ? n : N - 1];
+
+    const uint4 *wtile = wp + static_cast<int64_t>(ntile) * k_tiles * 64 + lane;
+    auto load_weights = [&](int32_t base, uint4 (&b)[KT]) {
+#pragma unroll
+        for (int u = 0; u < KT; ++u) {
+            int32_t kt = base + u;
+            kt = kt < kt_end ? kt : kt_end - 1;
+            kt = kt > 0 ? kt : 0;
+            const v4u t = __builtin_nontemporal_load(
+                reinterpret_cast<const v4u *>(wtile + static_cast<int64_t>(kt) * 64));
+            b[u] = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+    };
+    // The first batch of weights is requested before the front end, so the rotation runs
+    // under that round trip to memory.
+    uint4 b[KT];
+    load_weights(kt_begin, b);
+
+    // ---- front end: x (fp16) -> rotated, quantized int8 rows in LDS
+    {
+        using Seg = Segment<B>;
+        const int32_t segs_per_row = (K + Seg::SEG - 1) / Seg::SEG;
+        const int32_t total = T * segs_per_row;
+        for (int32_t sgi = wave; sgi < total; sgi += NWAVES) {
+            const int32_t i = sgi / segs_per_row, sidx = sgi - i * segs_per_row;
+            Seg sg;
+            sg.load_rotate(x + static_cast<int64_t>(i) * ldx, sidx, K, lane);
+            sg.quant_store(i < ep.n_vis ? c_vis : c_txt, reinterpret_cast<int8_t *>(smem) + i * pitch,
+                           sidx, lane);
+        }
+    }
+    __syncthreads();
+
+    v16i acc0, acc1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        acc0[r] = 0;
+        acc1[r] = 0;
+    }
+    const uint8_t *frag = smem + (l32 < T ? l32 : T - 1) * pitch + g * 32;
+
+    auto batch = [&](int32_t base, const uint4 (&bw)[KT]) {
+        uint4 a0[KT], a1[KT];
+#pragma unroll
+        for (int u = 0; u < KT; ++u) {
+            int32_t kt = base + u;
+            kt = kt < kt_end ? kt : kt_end - 1;
+            a0[u] = *reinterpret_cast<const uint4 *>(frag + kt * 64);
+            a1[u] = *reinterpret_cast<const uint4 *>(frag + kt * 64 + 16);
+        }
+#pragma unroll
+        for (int u = 0; u < KT; ++u) {
+            const uint32_t m = (base + u < kt_end) ? 0xFFFFFFFFu : 0u;     // wave-uniform
+            uint4 bb = bw[u];
+            bb.x &= m;
+            bb.y &= m;
+            bb.z &= m;
+            bb.w &= m;
+            v4i b0, b1;
+            unpack_w4x16(bb, b0, b1);
+            acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a0[u]), b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a1[u]), b1, acc1, 0, 0, 0);
+        }
+    };
+    if (kt_begin < kt_end) batch(kt_begin, b);             // its weights were requested up front
+    for (int32_t base = kt_begin + KT; base < kt_end; base += KT) {
+        load_weights(base, b);
+        batch(base, b);
+        // all memory and LDS reads of the batch first, then the arithmetic
+        __builtin_amdgcn_sched_group_barrier(0x020, KT, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * KT, 0);
+        __builtin_amdgcn_sched_group_barrier(0x00A, 18 * KT, 0);
+    }
+    __syncthreads();                                       // the sums below reuse the xq copy
+
+    // T <= 4: only accumulator registers r < 4 of lane group 0 hold valid rows
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wave][r][lane] = acc0[r] + acc1[r];
+    __syncthreads();
+    const float ws = __half2float(ws_h);
+    for (int r = wave; r < 4; r += NWAVES) {
+        const int32_t row = acc_row(r, g);
+        if (row < T && n < N) {
+            int32_t sum = 0;
+#pragma unroll
+            for (int w = 0; w < NWAVES; ++w) sum += red[w][r][lane];
+            store_out<kEpiStatic>(sum, row, n, ep, ws, y, ldy, nullptr, N);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ host side
 
 constexpr int kGemvMaxT = 32;
@@ -1030,4 +1152,74 @@ extern "C" int mquant_w4a8_linear_prefill(const void *x, int64_t ldx, const int3
     const int64_t xq_bytes = ceil_div(static_cast<int64_t>(T) * K, 256) * 256;
     return mquant_w4a8_gemm(xq, wp, w_scale, y, ldy, nullptr, T, N, K, n_vis, s_vis, s_txt,
                             static_cast<uint8_t *>(workspace) + xq_bytes, need - xq_bytes, stream);
+}
+
+namespace {
+
+constexpr int kDecodeFusedMaxT = 4;
+
+template <int B>
+int launch_decode_fused(const __half *x, int64_t ldx, const uint4 *wp, const __half *w_scale, __half *y,
+                        int64_t ldy, int32_t T, int32_t N, int32_t K, const Epilogue &ep, float c_vis,
+                        float c_txt, hipStream_t stream)
+{
+    const unsigned n_tiles = static_cast<unsigned>(ceil_div(N, 32));
+    const int64_t xq_bytes = static_cast<int64_t>(T) * (K + 16);
+    if (n_tiles >= 256) {
+        const size_t lds = static_cast<size_t>(xq_bytes > 8 * 4096 ? xq_bytes : 8 * 4096);
+        auto kern = w4a8_decode_fused_kernel<8, 4, B>;
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return MQUANT_ERR_HIP;
+        MQ_LAUNCH(kern, dim3(n_tiles), dim3(512), lds, stream, x, ldx, wp, w_scale, y, ldy, T, N, K, ep,
+                  c_vis, c_txt);
+    } else {
+        const size_t lds = static_cast<size_t>(xq_bytes > 16 * 4096 ? xq_bytes : 16 * 4096);
+        auto kern = w4a8_decode_fused_kernel<16, 4, B>;
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return MQUANT_ERR_HIP;
+        MQ_LAUNCH(kern, dim3(n_tiles), dim3(1024), lds, stream, x, ldx, wp, w_scale, y, ldy, T, N, K, ep,
+                  c_vis, c_txt);
+    }
+    return launch_status();
+}
+
+}  // namespace
+
+extern "C" int mquant_w4a8_linear_decode(const void *x, int64_t ldx, const uint8_t *wp,
+                                         const void *w_scale, void *y, int64_t ldy, int32_t T,
+                                         int32_t N, int32_t K, int32_t n_vis, float s_vis, float s_txt,
+                                         int32_t had_block, mquant_stream_t stream)
+{
+    if (T < 0 || N < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
+    if (T > kDecodeFusedMaxT) return MQUANT_ERR_UNSUPPORTED;
+    if (had_block != 1 && had_block != 128 && had_block != 512) return MQUANT_ERR_UNSUPPORTED;
+    if (K % kPackK != 0 || K > kMaxK || K % had_block != 0) return MQUANT_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(T) * (K + 16) > 150 * 1024) return MQUANT_ERR_UNSUPPORTED;
+    if (n_vis < 0 || n_vis > T) return MQUANT_ERR_BAD_SHAPE;
+    if (!(s_vis > 0.0f) || !(s_txt > 0.0f) || !isfinite(s_vis) || !isfinite(s_txt))
+        return MQUANT_ERR_BAD_SHAPE;
+    if (T == 0 || N == 0) return MQUANT_OK;
+    if (K == 0) return MQUANT_ERR_UNSUPPORTED;
+    if (ldx < K || ldy < N) return MQUANT_ERR_BAD_SHAPE;
+    if (!x || !wp || !w_scale || !y) return MQUANT_ERR_NULL;
+    if (ldx % 8 != 0 || !aligned_to(x, 16) || !aligned_to(wp, 16) || !aligned_to(w_scale, 2) ||
+        !aligned_to(y, 2))
+        return MQUANT_ERR_ALIGNMENT;
+    const double rb = sqrt(static_cast<double>(had_block));
+    const float c_vis = static_cast<float>(1.0 / (static_cast<double>(s_vis) * rb));
+    const float c_txt = static_cast<float>(1.0 / (static_cast<double>(s_txt) * rb));
+    Epilogue ep = {};
+    ep.n_vis = n_vis, ep.s_vis = s_vis, ep.s_txt = s_txt, ep.K = K;
+    hipStream_t stream_h = static_cast<hipStream_t>(stream);
+    const __half *xh = static_cast<const __half *>(x);
+    const uint4 *wpp = reinterpret_cast<const uint4 *>(wp);
+    const __half *wsc = static_cast<const __half *>(w_scale);
+    __half *yh = static_cast<__half *>(y);
+    switch (had_block) {
+    case 1: return launch_decode_fused<1>(xh, ldx, wpp, wsc, yh, ldy, T, N, K, ep, c_vis, c_txt, stream_h);
+    case 128: return launch_decode_fused<128>(xh, ldx, wpp, wsc, yh, ldy, T, N, K, ep, c_vis, c_txt, stream_h);
+    default: return launch_decode_fused<512>(xh, ldx, wpp, wsc, yh, ldy, T, N, K, ep, c_vis, c_txt, stream_h);
+    }
 }

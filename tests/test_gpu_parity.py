@@ -421,3 +421,41 @@ def test_measurement_probes_run(mq):
     torch.cuda.synchronize()
     assert mq.lib.mquant_probe_mfma_i8(-1, data.data_ptr(), 1 << 16, sink.data_ptr(), None) == mq.ERR_BAD_SHAPE
     assert mq.lib.mquant_probe_hbm_read(None, 16, sink.data_ptr(), None) == mq.ERR_NULL
+
+
+@pytest.mark.parametrize("T,N,K,B", [(1, 200, 896, 128), (1, 3584, 3584, 512), (4, 512, 3584, 512),
+                                     (3, 3584, 18944, 512), (2, 18944, 3584, 512), (1, 8192, 8192, 128),
+                                     (4, 264, 1024, 1)])
+def test_fused_decode_linear_equals_separate_entries_and_oracle(mq, T, N, K, B):
+    """Rotate + quantize + GEMV + dequant in one launch: same bits as the two-launch path,
+    and within 1e-3 of the oracle."""
+    say(f"fused decode T={T} N={N} K={K} B={B}")
+    rng = np.random.default_rng(T + N + K)
+    x = (rng.standard_normal((T, K)) * rng.uniform(0.5, 3.0, size=(T, 1))).astype(np.float16)
+    packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+    V = min(T, 1)
+    u = orc.hadamard_rotate(x, B)
+    s_vis = float(orc.static_scale_from_absmax(np.abs(u).max(), B))
+    s_txt = s_vis * 0.8
+    o = orc.w4a8_linear(x, [(0, V)], packed, w_scale, s_vis, s_txt, B)
+    wp = mq.w4_prepack(dev(packed))
+    y = mq.w4a8_linear_decode(dev(x), wp, dev(w_scale), N, V, s_vis, s_txt, B)
+    xq = mq.hadamard_quant_act(dev(x), V, s_vis, s_txt, B)
+    y2 = mq.w4a8_gemm(xq, wp, dev(w_scale), N, V, s_vis, s_txt)
+    assert torch.equal(y, y2)
+    check_y(y.cpu().numpy(), o["ref"], "fused decode")
+
+
+def test_fused_decode_linear_argument_errors(mq):
+    x = torch.zeros((5, 512), dtype=torch.float16, device="cuda")
+    wp = torch.zeros(mq.w4_prepacked_bytes(32, 512), dtype=torch.uint8, device="cuda")
+    ws = torch.ones(32, dtype=torch.float16, device="cuda")
+    y = torch.empty((5, 32), dtype=torch.float16, device="cuda")
+    call = lambda T, B: mq.lib.mquant_w4a8_linear_decode(x.data_ptr(), 512, wp.data_ptr(), ws.data_ptr(),
+                                                          y.data_ptr(), 32, T, 32, 512, 0, 1.0, 1.0, B, None)
+    assert call(5, 512) == mq.ERR_UNSUPPORTED
+    assert call(1, 256) == mq.ERR_UNSUPPORTED
+    assert call(0, 512) == mq.OK
+    assert call(1, 512) == mq.OK
+    torch.cuda.synchronize()
