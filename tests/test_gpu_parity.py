@@ -459,3 +459,26 @@ def test_fused_decode_linear_argument_errors(mq):
     assert call(0, 512) == mq.OK
     assert call(1, 512) == mq.OK
     torch.cuda.synchronize()
+
+
+def test_gemm_seeded_shape_sweep(mq):
+    """Thirty seeded shapes across the dispatch boundaries (GEMV / both GEMM tiles / row slabs for
+    K % 128 != 0, one k-block, single channels, N not a multiple of 8): accumulators bit for bit."""
+    rng = np.random.default_rng(2024)
+    shapes = [(33, 40, 128), (64, 1, 64), (257, 9, 192), (129, 257, 128), (40, 600, 2048), (300, 31, 1024)]
+    while len(shapes) < 30:
+        shapes.append((int(rng.integers(1, 301)), int(rng.integers(1, 601)), 64 * int(rng.integers(1, 33))))
+    for T, N, K in shapes:
+        say(f"sweep T={T} N={N} K={K}")
+        xq = rng.integers(-128, 128, size=(T, K), dtype=np.int8)
+        packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+        w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+        V = int(rng.integers(0, T + 1))
+        acc_want = orc.gemm_i8_i4_i32(xq, orc.unpack_w4(packed))
+        ref, _ = orc.dequant(acc_want, V, 0.07, 0.009, w_scale)
+        acc = torch.full((T, N), -7, dtype=torch.int32, device="cuda")
+        y = mq.w4a8_gemm(dev(xq), mq.w4_prepack(dev(packed)), dev(w_scale), N, V, 0.07, 0.009, acc_out=acc)
+        assert (acc.cpu().numpy() == acc_want).all(), (T, N, K)
+        check_y(y.cpu().numpy(), ref, f"sweep {(T, N, K)}")
+        y2 = mq.w4a8_gemm(dev(xq), mq.w4_prepack(dev(packed)), dev(w_scale), N, V, 0.07, 0.009)
+        check_y(y2.cpu().numpy(), ref, f"sweep, no acc_out {(T, N, K)}")
