@@ -466,6 +466,49 @@ def w4a8_linear_dynamic(x_u: np.ndarray, w_packed: np.ndarray, w_scale: np.ndarr
     return {"xq": xq, "s_rows": s_rows, "acc": acc, "ref": ref, "y": y}
 
 
+# --------------------------------------------------------------------------
+# Weight-only setting (Table 13: W4 with a group size of 128, activations kept in
+# the 16-bit type; group-wise weight granularity of the appendix on quantization
+# granularity).  The weight is dequantised to the 16-bit type and the GEMM runs in
+# it (the "dequant W" pipeline that Table 3 lists for weight-only methods); fp16 is the 16-bit type of this path.
+
+def quantize_weight_groups_int4(Wt: np.ndarray, group: int = 128):
+    """Group-wise symmetric int4 (Eq. (2), b = 4, z = 0, round to nearest even):
+    Wt is [N, K]; every run of `group` input channels of an output channel has its
+    own scale max|w|/7, rounded to fp16 before the codes are taken (all-zero group:
+    scale 1).  Returns (codes int8 [N, K] in [-8, 7], scales fp16 [N, K/group])."""
+    Wt = np.asarray(Wt, dtype=np.float64)
+    N, K = Wt.shape
+    assert K % group == 0
+    Wg = Wt.reshape(N, K // group, group)
+    amax = np.abs(Wg).max(axis=2)
+    scale = np.where(amax > 0, amax / 7.0, 1.0).astype(np.float16)
+    q = np.clip(np.rint(Wg / scale.astype(np.float64)[:, :, None]), -8, 7).astype(np.int8)
+    return q.reshape(N, K), scale
+
+
+def dequant_weight_groups_f16(wq: np.ndarray, scales: np.ndarray, group: int = 128) -> np.ndarray:
+    """fp16 weight W~[n, k] = fp16(wq[n, k] * scales[n, k // group]): the product of
+    an int4 code and an fp16 scale is exact in double; one rounding to fp16."""
+    wq = np.asarray(wq)
+    N, K = wq.shape
+    sc = np.asarray(scales)
+    assert sc.dtype == np.float16 and sc.shape == (N, K // group)
+    prod = wq.astype(np.float64) * np.repeat(sc.astype(np.float64), group, axis=1)
+    return prod.astype(np.float16)
+
+
+def w4g128_linear(x: np.ndarray, wq: np.ndarray, scales: np.ndarray, group: int = 128):
+    """y = x W~^T with fp16 x [T, K] and the dequantised fp16 weight, summed in
+    double.  Returns (ref fp64 [T, N], mag fp64 [T, N]) where mag = sum_k |x_k W~_nk|
+    is the magnitude a floating-point accumulation error is measured against."""
+    x = np.asarray(x)
+    assert x.dtype == np.float16
+    Wd = dequant_weight_groups_f16(wq, scales, group).astype(np.float64)
+    xd = x.astype(np.float64)
+    return xd @ Wd.T, np.abs(xd) @ np.abs(Wd).T
+
+
 def w4a8_linear(x: np.ndarray, vis_spans: Sequence[Tuple[int, int]], w_packed: np.ndarray,
                 w_scale: np.ndarray, s_vis: float, s_txt: float, B: int,
                 rows=None, cols=None) -> dict:
