@@ -350,6 +350,43 @@ int mquant_aifs_attention(const void *q_dev, int64_t ldq, const void *k_dev, int
                           mquant_stream_t stream);
 
 /* -------------------------------------------------------------------------
+ * Weight-only W4 linear with group-wise scales (the weight-only setting of
+ * Table 13: int4 weight, group size 128, 16-bit activations; group-wise
+ * granularity as in the appendix on quantization granularity).  The weight is
+ * dequantised to fp16 on its way into the matrix core:
+ *   W~[n, k] = fp16(wq[n, k] * s[n, k / 128])        one rounding
+ *   y[i, n]  = fp16(sum_k x[i, k] * W~[n, k])        products exact, fp32 sums
+ * ---------------------------------------------------------------------- */
+
+/* Bytes of the kernel-private layout (weight tiles, then the scale table) for an
+ * [N, K] matrix.  Negative status: ERR_BAD_SHAPE, ERR_UNSUPPORTED (K % 128 != 0). */
+int64_t mquant_w4g128_prepacked_bytes(int32_t N, int32_t K);
+
+/*
+ * DEVICE, one-off.  Reorders
+ *   w_canonical_dev : uint8 [N, K/2], nibble order as for mquant_w4_prepack, 4-byte aligned
+ *   scales_dev      : fp16 [N, K/128], scale of output channel n and channel group k/128
+ * into out_dev (mquant_w4g128_prepacked_bytes(N, K) bytes, 16-byte aligned).
+ * The layout differs from mquant_w4_prepack's: the two are not interchangeable.
+ */
+int mquant_w4g128_prepack(const uint8_t *w_canonical_dev, const void *scales_dev, uint8_t *out_dev,
+                          int32_t N, int32_t K, mquant_stream_t stream);
+
+/*
+ * DEVICE.  y = x W~^T as defined above.
+ *   x_dev : fp16 [T, ldx], 16-byte aligned, ldx >= K and ldx % 8 == 0 (read only)
+ *   w_prepacked_dev : output of mquant_w4g128_prepack for the same (N, K)
+ *   y_dev : fp16 [T, ldy] (written: columns 0..N-1 of every row), ldy >= N; 16-byte
+ *           stores are used when N % 8 == 0, ldy % 8 == 0 and y_dev is 16-byte aligned
+ * The summation order is the matrix core's and is not specified; results agree with
+ * a double-precision sum to within fp32 accumulation error plus the final fp16 rounding.
+ * T == 0 or N == 0 is a no-op.  Errors: ERR_BAD_SHAPE, ERR_UNSUPPORTED (K % 128 != 0 or
+ * K == 0), ERR_NULL, ERR_ALIGNMENT, ERR_HIP.
+ */
+int mquant_w4g128_gemm(const void *x_dev, int64_t ldx, const uint8_t *w_prepacked_dev, void *y_dev,
+                       int64_t ldy, int32_t T, int32_t N, int32_t K, mquant_stream_t stream);
+
+/* -------------------------------------------------------------------------
  * Measurement probes.  Not part of the method: they measure what this chip
  * attains on the two resources the path is bound by (for the benchmark's
  * "attainable" figures).  Both are DEVICE calls, asynchronous like the rest.

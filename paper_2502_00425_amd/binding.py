@@ -32,6 +32,7 @@ EXPORTS = (
     "mquant_hadamard_quant_act_bits",
     "mquant_probe_mfma_i8_ops", "mquant_probe_mfma_i8", "mquant_probe_hbm_read",
     "mquant_w4a8_linear_decode",
+    "mquant_w4g128_prepacked_bytes", "mquant_w4g128_prepack", "mquant_w4g128_gemm",
 )
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGNMENT = 0, -1, -2, -3, -4, -5, -6
@@ -82,13 +83,17 @@ def _load() -> ctypes.CDLL:
     lib.mquant_aifs_attention_workspace_bytes.argtypes = [i32, i32, i32]
     lib.mquant_aifs_attention.argtypes = [p, i64, p, i64, p, i64, p, i64, p, i32, i32, i32, i32, p, i64, p]
     lib.mquant_w4a8_linear_decode.argtypes = [p, i64, p, p, p, i64, i32, i32, i32, i32, f32, f32, i32, p]
+    lib.mquant_w4g128_prepacked_bytes.restype = i64
+    lib.mquant_w4g128_prepacked_bytes.argtypes = [i32, i32]
+    lib.mquant_w4g128_prepack.argtypes = [p, p, p, i32, i32, p]
+    lib.mquant_w4g128_gemm.argtypes = [p, i64, p, p, i64, i32, i32, i32, p]
     lib.mquant_probe_mfma_i8_ops.restype = i64
     lib.mquant_probe_mfma_i8_ops.argtypes = [i32]
     lib.mquant_probe_mfma_i8.argtypes = [i32, p, i64, p, p]
     lib.mquant_probe_hbm_read.argtypes = [p, i64, p, p]
     for name in EXPORTS:
         if name not in ("mquant_status_string", "mquant_w4_prepacked_bytes", "mquant_aifs_attention_workspace_bytes",
-                        "mquant_probe_mfma_i8_ops",
+                        "mquant_probe_mfma_i8_ops", "mquant_w4g128_prepacked_bytes",
                         "mquant_w4a8_workspace_bytes", "mquant_w4a8_linear_prefill_workspace_bytes",
                         "mquant_version"):
             getattr(lib, name).restype = ctypes.c_int
@@ -363,4 +368,36 @@ def w4a8_linear_decode(x, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float
     _check(lib.mquant_w4a8_linear_decode(_dp(x), x.stride(0), _dp(w_prepacked), _dp(w_scale), _dp(out),
                                          out.stride(0), T, N, K, n_vis, s_vis, s_txt, had_block,
                                          _stream()), "mquant_w4a8_linear_decode")
+    return out
+
+
+def w4g128_prepacked_bytes(N: int, K: int) -> int:
+    n = int(lib.mquant_w4g128_prepacked_bytes(N, K))
+    if n < 0:
+        raise MQuantError(n, "mquant_w4g128_prepacked_bytes")
+    return n
+
+
+def w4g128_prepack(w_canonical, scales, out=None):
+    """w_canonical uint8 [N, K/2], scales fp16 [N, K/128] -> the weight-only kernel's layout."""
+    import torch
+    N, K2 = w_canonical.shape
+    K = 2 * K2
+    if out is None:
+        out = torch.empty(w4g128_prepacked_bytes(N, K), dtype=torch.uint8, device=w_canonical.device)
+    if tuple(scales.shape) != (N, K // 128) or not scales.is_contiguous():
+        raise MQuantError(ERR_BAD_SHAPE, "w4g128_prepack: scales must be contiguous [N, K/128]")
+    _check(lib.mquant_w4g128_prepack(_dp(w_canonical), _dp(scales), _dp(out), N, K, _stream()),
+           "mquant_w4g128_prepack")
+    return out
+
+
+def w4g128_gemm(x, w_prepacked, N: int, out=None):
+    """x fp16 [T, K] (row stride in elements) -> y fp16 [T, N] = x W~^T, group-wise dequantised weight."""
+    import torch
+    T, K = x.shape
+    if out is None:
+        out = torch.empty((T, N), dtype=torch.float16, device=x.device)
+    _check(lib.mquant_w4g128_gemm(_dp(x), x.stride(0) if T > 0 else K, _dp(w_prepacked), _dp(out),
+                                  out.stride(0) if T > 0 else N, T, N, K, _stream()), "mquant_w4g128_gemm")
     return out

@@ -13,7 +13,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIB_DIR, "libmquant.so")
-SOURCES = ["aifs.hip", "hadamard_quant.hip", "w4a8_gemm.hip", "attention.hip", "probes.hip"]
+SOURCES = ["aifs.hip", "hadamard_quant.hip", "w4a8_gemm.hip", "attention.hip", "probes.hip",
+           "w4g128_gemm.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

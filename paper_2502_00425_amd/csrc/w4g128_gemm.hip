@@ -1,0 +1,363 @@
+// Weight-only W4 linear with group-wise scales (the weight-only setting of
+// Table 13: int4 weight, one fp16 scale per 128 input channels of an output
+// channel, 16-bit activations; group-wise granularity as in the appendix on
+// quantization granularity).
+//
+//   W~[n, k] = fp16(wq[n, k] * s[n, k / 128])          (one rounding)
+//   y[i, n]  = fp16(sum_k x[i, k] * W~[n, k])           (fp32 accumulation)
+//
+// Matrix core: v_mfma_f32_32x32x16_f16.  A = fp16 activations (M = tokens), staged
+// through LDS; B = weights, dequantised in registers on their way into the MFMA.
+// Lane l supplies row/column l % 32 and the 8 consecutive k of slot group l / 32.
+// The contraction order inside a 64-channel k-tile is free as long as A and B
+// agree: MFMA step s of a tile contracts channels {s*8..s*8+7} (lanes 0..31) and
+// {32+s*8..32+s*8+7} (lanes 32..63), so that the 16 bytes a lane fetches from the
+// prepacked weight are its B operands of all four steps.
+//
+// Prepacked weights: [n_tile][k_tile][lane][16 bytes] as for the W4A8 kernels
+// (tile = 32 output x 64 input channels, lane (n % 32) + 32 * g holds channels
+// 64*k_tile + 32*g .. +31 of row n), but inside a dword of 8 channels nibble j
+// holds channel 2j and nibble j + 4 channel 2j + 1 (j = 0..3), each stored as
+// code + 8.  (v >> 4j) & 0x000F000F then is a pair of adjacent channels in the
+// two halves of a dword; OR-ing 0x6400 into each half makes the fp16 number
+// 1024 + code + 8, from which 1032 is subtracted exactly before the multiply by
+// the scale -- two packed fp16 operations per pair and no integer->float convert.
+// The scale table follows the weight tiles, transposed to [K/128][N padded to 32]
+// so that the 32 lanes of a tile read consecutive halves.
+#include <hip/hip_fp16.h>
+
+#include "mquant_internal.h"
+
+using namespace mquant;
+
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kGroup = 128;               // input channels per weight scale
+constexpr int kAPitch = 144;              // bytes per LDS row of the A tile: 64 halves + 16 pad
+
+// 16-byte reads of 16 consecutive rows at pitch 144 B start at banks 36 r mod 64 =
+// {0,36,8,44,16,52,24,60,32,4,40,12,48,20,56,28}: the 64 banks exactly once.
+
+__global__ __launch_bounds__(256) void g128_prepack_kernel(
+    const uint8_t *__restrict__ w, const __half *__restrict__ scales, uint32_t *__restrict__ out_w,
+    __half *__restrict__ out_s, int32_t N, int32_t K, int32_t n_tiles, int32_t k_tiles)
+{
+    const int64_t total = static_cast<int64_t>(n_tiles) * k_tiles * 64 * 4;     // dwords
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * 256;
+    for (int64_t o = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; o < total; o += stride) {
+        const int d = static_cast<int>(o & 3);
+        const int lane = static_cast<int>((o >> 2) & 63);
+        const int64_t tile = o >> 8;
+        const int32_t kt = static_cast<int32_t>(tile % k_tiles);
+        const int32_t nt = static_cast<int32_t>(tile / k_tiles);
+        const int32_t n = nt * kPackN + (lane & 31);
+        const int32_t k0 = kt * kPackK + (lane >> 5) * 32 + d * 8;
+        uint32_t v = 0x88888888u;                                   // code 0 everywhere
+        if (n < N) {
+            const uint32_t src =
+                *reinterpret_cast<const uint32_t *>(w + static_cast<int64_t>(n) * (K / 2) + k0 / 2) ^
+                0x88888888u;                                        // nibble c of src = channel k0 + c
+            v = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v |= ((src >> (4 * (2 * j))) & 0xFu) << (4 * j);
+                v |= ((src >> (4 * (2 * j + 1))) & 0xFu) << (4 * (j + 4));
+            }
+        }
+        out_w[o] = v;
+    }
+    const int32_t n_pad = n_tiles * kPackN;
+    const int64_t total_s = static_cast<int64_t>(K / kGroup) * n_pad;
+    for (int64_t o = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; o < total_s; o += stride) {
+        const int32_t n = static_cast<int32_t>(o % n_pad);
+        const int32_t kg = static_cast<int32_t>(o / n_pad);
+        out_s[o] = n < N ? scales[static_cast<int64_t>(n) * (K / kGroup) + kg] : __float2half(1.0f);
+    }
+}
+
+// One dword of prepacked weights -> 8 fp16 weights (channels in ascending order),
+// each fp16(code * scale); s2 holds the scale in both halves.
+__device__ __forceinline__ void dequant8(uint32_t v, v2h s2, uint32_t out[4])
+{
+    const v2h bias = {static_cast<_Float16>(1032.0f), static_cast<_Float16>(1032.0f)};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t bits = ((v >> (4 * j)) & 0x000F000Fu) | 0x64006400u;
+        v2h h = __builtin_bit_cast(v2h, bits);
+        h = (h - bias) * s2;                      // the difference is exact; one rounding
+        out[j] = __builtin_bit_cast(uint32_t, h);
+    }
+}
+
+__device__ __forceinline__ int acc_row(int r, int g) { return (r >> 2) * 8 + g * 4 + (r & 3); }
+
+// Work-group id -> (tm, tn): the eight XCDs (work-groups are dealt to them round
+// robin) each get a contiguous run of a tile order that walks bands of `band`
+// tile-rows, so the tiles an XCD holds at a time share few row and column panels.
+__device__ __forceinline__ void tile_of_group(int32_t id, int32_t tiles_m, int32_t tiles_n,
+                                              int32_t band, int32_t &tm, int32_t &tn)
+{
+    const int32_t total = tiles_m * tiles_n;
+    const int32_t per = total / 8, rem = total % 8;
+    const int32_t xcd = id % 8, local = id / 8;
+    const int32_t t = xcd * per + (xcd < rem ? xcd : rem) + local;
+    const int32_t band_tiles = band * tiles_n;
+    const int32_t b = t / band_tiles;
+    const int32_t in_band = t - b * band_tiles;
+    const int32_t rows = (tiles_m - b * band) < band ? (tiles_m - b * band) : band;
+    tm = b * band + in_band % rows;
+    tn = in_band / rows;
+}
+
+// Work-group tile BM x BN, WM x WN wavefronts.  K advances 64 channels at a time;
+// the A tile of the next step is fetched into registers while the current one is
+// multiplied, then written to the other LDS buffer: one barrier per step.
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
+    const __half *__restrict__ x, int64_t ldx, const v4u *__restrict__ wp,
+    const __half *__restrict__ sT, __half *__restrict__ y, int64_t ldy, int32_t T, int32_t N,
+    int32_t K, int32_t tiles_m, int32_t tiles_n, int32_t n_tiles32, int32_t wide_store,
+    int32_t band)
+{
+    constexpr int NW = WM * WN, NTHR = NW * 64;
+    constexpr int MT = BM / WM / 32, NT = BN / WN / 32;
+    constexpr int A_BUF = BM * kAPitch;
+    constexpr int A_LOADS = BM * 8 / NTHR;            // 16-byte chunks of the A tile per thread
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && (BM * 8) % NTHR == 0, "tile shape");
+    constexpr int PATCH = NW * 32 * (NT * 64 + 16);  // epilogue patches, one per wave
+    constexpr int SMEM = 2 * A_BUF > PATCH ? 2 * A_BUF : PATCH;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int wm = wave / WN, wn = wave % WN;
+    int32_t tm, tn;
+    tile_of_group(blockIdx.x, tiles_m, tiles_n, band, tm, tn);
+    const int32_t row0 = tm * BM;
+    const int32_t ntile0 = tn * (BN / 32);
+    const int32_t k_tiles = K / kPackK;
+    const int32_t n_pad = n_tiles32 * kPackN;
+
+    // n-tiles of this wave, clamped to the last real tile (columns beyond N are never stored)
+    int32_t my_tile[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int32_t t = ntile0 + wn * NT + nt;
+        my_tile[nt] = t < n_tiles32 ? t : n_tiles32 - 1;
+    }
+
+    v4u areg[A_LOADS];
+    auto load_a = [&](int32_t kt) {
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i) {
+            const int c = tid + i * NTHR;
+            const int32_t row = row0 + (c >> 3);
+            v4u v = {0u, 0u, 0u, 0u};
+            if (row < T)
+                v = *reinterpret_cast<const v4u *>(x + static_cast<int64_t>(row) * ldx +
+                                                   static_cast<int64_t>(kt) * kPackK + (c & 7) * 8);
+            areg[i] = v;
+        }
+    };
+    auto store_a = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i) {
+            const int c = tid + i * NTHR;
+            *reinterpret_cast<v4u *>(smem + buf * A_BUF + (c >> 3) * kAPitch + (c & 7) * 16) = areg[i];
+        }
+    };
+    auto load_b = [&](int32_t kt, v4u (&b)[NT]) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            b[nt] = wp[(static_cast<int64_t>(my_tile[nt]) * k_tiles + kt) * 64 + lane];
+    };
+    auto load_s = [&](int32_t kt, v2h (&s)[NT]) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const _Float16 v = __builtin_bit_cast(
+                _Float16, sT[static_cast<int64_t>(kt / 2) * n_pad + my_tile[nt] * kPackN + l32]);
+            s[nt] = v2h{v, v};
+        }
+    };
+
+    v16f acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
+
+    v4u bcur[NT], bnext[NT];
+    v2h scur[NT], snext[NT];
+    load_a(0);
+    load_b(0, bcur);
+    load_s(0, scur);
+    store_a(0);
+    __syncthreads();
+
+    for (int32_t kt = 0; kt < k_tiles; ++kt) {
+        const bool more = kt + 1 < k_tiles;
+        if (more) {
+            load_a(kt + 1);
+            load_b(kt + 1, bnext);
+            if (((kt + 1) & 1) == 0) {                 // a new group of 128 channels starts
+                load_s(kt + 1, snext);
+            } else {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) snext[nt] = scur[nt];
+            }
+        }
+        const uint8_t *abase =
+            smem + (kt & 1) * A_BUF + (wm * MT * 32 + l32) * kAPitch + g * 64;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            v8h bfr[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                uint32_t d[4];
+                dequant8(bcur[nt][s], scur[nt], d);
+                const v4u packed = {d[0], d[1], d[2], d[3]};
+                bfr[nt] = __builtin_bit_cast(v8h, packed);
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const v8h afr = *reinterpret_cast<const v8h *>(abase + mt * 32 * kAPitch + s * 16);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr, bfr[nt], acc[mt][nt], 0, 0, 0);
+            }
+        }
+        if (more) {
+            store_a((kt + 1) & 1);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                bcur[nt] = bnext[nt];
+                scur[nt] = snext[nt];
+            }
+        }
+        __syncthreads();
+    }
+
+    const int32_t wave_row0 = row0 + wm * (BM / WM);
+    const int32_t wave_n0 = (ntile0 + wn * NT) * 32;
+
+    if (!wide_store) {
+        // every lane stores its own 2-byte results
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int32_t n = wave_n0 + nt * 32 + l32;
+            if (n >= N) continue;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int32_t row = wave_row0 + mt * 32 + acc_row(r, g);
+                    if (row < T) y[static_cast<int64_t>(row) * ldy + n] = __float2half_rn(acc[mt][nt][r]);
+                }
+        }
+        return;
+    }
+
+    // Wide stores: the MFMA result has a lane per column; each wave turns 32 rows x
+    // NT*32 columns through its own LDS patch (the A buffers are free after the last
+    // barrier) and stores 16 bytes per lane.
+    constexpr int ROWB = NT * 64 + 16;
+    constexpr int LPR = NT * 64 / 16;
+    constexpr int RPI = 64 / LPR;
+    static_assert(NW * 32 * ROWB == PATCH, "patch size");
+    uint8_t *patch = smem + wave * (32 * ROWB);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rl = acc_row(r, g);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                *reinterpret_cast<__half *>(patch + rl * ROWB + (nt * 32 + l32) * 2) =
+                    __float2half_rn(acc[mt][nt][r]);
+        }
+#pragma unroll
+        for (int q = 0; q < 32 / RPI; ++q) {
+            const int rl = q * RPI + lane / LPR;
+            const int c = lane % LPR;
+            const v4u v = *reinterpret_cast<const v4u *>(patch + rl * ROWB + c * 16);
+            const int32_t row = wave_row0 + mt * 32 + rl;
+            const int32_t n = wave_n0 + c * 8;
+            if (row < T && n < N)                                  // N % 8 == 0 on this path
+                *reinterpret_cast<v4u *>(y + static_cast<int64_t>(row) * ldy + n) = v;
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN>
+int launch_g128(const __half *x, int64_t ldx, const uint8_t *wp, __half *y, int64_t ldy, int32_t T,
+                int32_t N, int32_t K, hipStream_t stream)
+{
+    const int32_t n_tiles32 = static_cast<int32_t>(ceil_div(N, kPackN));
+    const int32_t tiles_m = static_cast<int32_t>(ceil_div(T, BM));
+    const int32_t tiles_n = static_cast<int32_t>(ceil_div(N, BN));
+    const int64_t w_bytes = static_cast<int64_t>(n_tiles32) * (K / kPackK) * kPackTileBytes;
+    const __half *sT = reinterpret_cast<const __half *>(wp + w_bytes);
+    const int32_t wide = (N % 8 == 0 && ldy % 8 == 0 && aligned_to(y, 16)) ? 1 : 0;
+    const int32_t band = tiles_m < 4 ? tiles_m : 4;
+    MQ_LAUNCH((w4g128_gemm_kernel<BM, BN, WM, WN>), dim3(tiles_m * tiles_n), dim3(WM * WN * 64), 0,
+              stream, x, ldx, reinterpret_cast<const v4u *>(wp), sT, y, ldy, T, N, K, tiles_m,
+              tiles_n, n_tiles32, wide, band);
+    return launch_status();
+}
+
+}  // namespace
+
+extern "C" int64_t mquant_w4g128_prepacked_bytes(int32_t N, int32_t K)
+{
+    if (N < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
+    if (K % kGroup != 0) return MQUANT_ERR_UNSUPPORTED;
+    const int64_t n_tiles = ceil_div(N, kPackN);
+    return n_tiles * (K / kPackK) * kPackTileBytes + static_cast<int64_t>(K / kGroup) * n_tiles * kPackN * 2;
+}
+
+extern "C" int mquant_w4g128_prepack(const uint8_t *w, const void *scales, uint8_t *out, int32_t N,
+                                     int32_t K, mquant_stream_t stream)
+{
+    if (N < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
+    if (K % kGroup != 0) return MQUANT_ERR_UNSUPPORTED;
+    if (N == 0 || K == 0) return MQUANT_OK;
+    if (!w || !scales || !out) return MQUANT_ERR_NULL;
+    if (!aligned_to(w, 4) || !aligned_to(out, 16) || !aligned_to(scales, 2)) return MQUANT_ERR_ALIGNMENT;
+    const int32_t n_tiles = static_cast<int32_t>(ceil_div(N, kPackN));
+    const int32_t k_tiles = K / kPackK;
+    const int64_t w_bytes = static_cast<int64_t>(n_tiles) * k_tiles * kPackTileBytes;
+    const int64_t dwords = w_bytes / 4;
+    const int grid = static_cast<int>(dwords / 256 < 4096 ? (dwords / 256 > 0 ? dwords / 256 : 1) : 4096);
+    MQ_LAUNCH(g128_prepack_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream), w,
+              static_cast<const __half *>(scales), reinterpret_cast<uint32_t *>(out),
+              reinterpret_cast<__half *>(out + w_bytes), N, K, n_tiles, k_tiles);
+    return launch_status();
+}
+
+extern "C" int mquant_w4g128_gemm(const void *x, int64_t ldx, const uint8_t *wp, void *y,
+                                  int64_t ldy, int32_t T, int32_t N, int32_t K,
+                                  mquant_stream_t stream)
+{
+    if (T < 0 || N < 0 || K < 0 || ldx < K || ldy < N) return MQUANT_ERR_BAD_SHAPE;
+    if (K % kGroup != 0) return MQUANT_ERR_UNSUPPORTED;
+    if (T == 0 || N == 0) return MQUANT_OK;
+    if (K == 0) return MQUANT_ERR_UNSUPPORTED;
+    if (!x || !wp || !y) return MQUANT_ERR_NULL;
+    if (!aligned_to(x, 16) || ldx % 8 != 0 || !aligned_to(wp, 16) || !aligned_to(y, 2))
+        return MQUANT_ERR_ALIGNMENT;
+    const __half *xh = static_cast<const __half *>(x);
+    __half *yh = static_cast<__half *>(y);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // Few tokens: narrow tiles so that the weight stream is spread over all CUs.
+    if (T <= 64) return launch_g128<64, 128, 2, 4>(xh, ldx, wp, yh, ldy, T, N, K, st);
+    const int64_t big = ceil_div(T, 256) * ceil_div(N, 256);
+    if (big >= 192) return launch_g128<256, 256, 2, 4>(xh, ldx, wp, yh, ldy, T, N, K, st);
+    return launch_g128<128, 128, 2, 4>(xh, ldx, wp, yh, ldy, T, N, K, st);
+}
