@@ -30,6 +30,7 @@ if ROOT not in sys.path:
 METRIC = "W4A8 linear throughput: prefill int8 TOPS (% MFMA peak); decode GB/s (% HBM)"
 INT8_MFMA_PEAK_TOPS = 5000.0       # MI355X dense int8, published
 HBM_PEAK_GBPS = 8000.0             # MI355X HBM3E, published
+FP16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense fp16, published
 # HBM-side bytes per GEMM launch (mean of the four launches of a step) from the two rocprofv3
 # --pmc runs summarised in profiles/gemm_c1_prefill_hbm_traffic_pmc.md (FETCH_SIZE x 2.000,
 # WRITE_SIZE x 1.000, factors from a plain 1 GiB copy; includes the split-K partials of down).  A counter run cannot happen inside
@@ -49,6 +50,7 @@ def parse_args():
     ap.add_argument("--no-attention", action="store_true", help="skip the attention / RoPE leg")
     ap.add_argument("--no-rms", action="store_true", help="skip the RMS split-path leg")
     ap.add_argument("--no-dynamic", action="store_true", help="skip the per-token dynamic baseline leg")
+    ap.add_argument("--no-weight-only", action="store_true", help="skip the weight-only (W4 group 128) leg")
     ap.add_argument("--no-graphs", action="store_true",
                     help="time the decode loop with plain launches instead of one HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -372,6 +374,10 @@ def main():
     if not args.no_attention:
         result["attention"] = bench_attention(args, torch, mq, wl, np)
 
+    # ------------------- weight-only W4 group-128 linears on the same shapes (context, next row 4)
+    if not args.no_weight_only:
+        result["weight_only_g128"] = bench_weight_only(args, torch, mq, lin, T, per_proj_ms)
+
     # ------------------------------------------------------------------ decode
     if not args.no_decode:
         result["decode"] = bench_decode(args, torch, mq, wl)
@@ -381,6 +387,50 @@ def main():
         result["cpu_baseline"] = cpu_baseline(args, np, w, lin, V)
 
     print(json.dumps(result), flush=True)
+
+
+def bench_weight_only(args, torch, mq, lin, T, w4a8_gemm_ms):
+    """The four projections of the prefill workload as weight-only linears: fp16 activations
+    straight into an fp16 MFMA GEMM whose weight operand is dequantised (int4, one fp16 scale per
+    128 input channels) in registers.  Random codes and scales; no rotation, no quantizer."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(6100)
+    out = {"scheme": "W4 group 128, A fp16 (dequantise in registers, fp16 MFMA, fp32 accumulate)",
+           "per_projection": {}}
+    total_us, flops = 0.0, 0.0
+    for proj, l in lin.items():
+        K, N = l["K"], l["N"]
+        wq = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device="cuda", generator=gen)
+        sc = (torch.rand((N, K // 128), device="cuda", generator=gen) * 0.008 + 0.002).to(torch.float16)
+        wp = mq.w4g128_prepack(wq, sc)
+        del wq
+        y = l["y"]
+        fn = lambda: mq.w4g128_gemm(l["x"], wp, N, out=y)
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                fn()
+            e1.record()
+            e1.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 100.0)      # us per launch
+        fl = 2.0 * T * K * N
+        out["per_projection"][proj] = {
+            "us": round(best, 2), "TFLOPs": round(fl / best / 1e6, 1),
+            "w4a8_gemm_us": round(w4a8_gemm_ms[proj] * 1e3, 2)}
+        total_us += best
+        flops += fl
+        del wp
+    out["us_per_step"] = round(total_us, 2)
+    out["TFLOPs"] = round(flops / total_us / 1e6, 1)
+    out["frac_of_fp16_mfma_peak"] = round(flops / total_us / 1e6 / FP16_MFMA_PEAK_TFLOPS, 4)
+    out["w4a8_gemm_us_per_step"] = round(sum(w4a8_gemm_ms.values()) * 1e3, 2)
+    return out
 
 
 def bench_attention(args, torch, mq, wl, np):

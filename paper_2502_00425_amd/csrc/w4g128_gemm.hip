@@ -80,18 +80,28 @@ __global__ __launch_bounds__(256) void g128_prepack_kernel(
     }
 }
 
+// (a & mask) | c in one VALU operation (the compiler emits an AND and an OR when both
+// constants are literals: a VOP3 instruction of this ISA takes no literal operand).
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(c));
+    return r;
+}
+
 // One dword of prepacked weights -> 8 fp16 weights (channels in ascending order),
 // each fp16(code * scale); s2 holds the scale in both halves.
-__device__ __forceinline__ void dequant8(uint32_t v, v2h s2, uint32_t out[4])
+__device__ __forceinline__ v4u dequant8(uint32_t v, v2h s2, uint32_t mask, uint32_t magic)
 {
     const v2h bias = {static_cast<_Float16>(1032.0f), static_cast<_Float16>(1032.0f)};
+    v4u out;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const uint32_t bits = ((v >> (4 * j)) & 0x000F000Fu) | 0x64006400u;
-        v2h h = __builtin_bit_cast(v2h, bits);
+        v2h h = __builtin_bit_cast(v2h, and_or(v >> (4 * j), mask, magic));
         h = (h - bias) * s2;                      // the difference is exact; one rounding
         out[j] = __builtin_bit_cast(uint32_t, h);
     }
+    return out;
 }
 
 __device__ __forceinline__ int acc_row(int r, int g) { return (r >> 2) * 8 + g * 4 + (r & 3); }
@@ -151,18 +161,19 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
         my_tile[nt] = t < n_tiles32 ? t : n_tiles32 - 1;
     }
 
+    // Rows past T read row T - 1 again: their results are never stored.
     v4u areg[A_LOADS];
+    const __half *arow[A_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) {
+        const int c = tid + i * NTHR;
+        const int32_t row = row0 + (c >> 3);
+        arow[i] = x + static_cast<int64_t>(row < T ? row : T - 1) * ldx + (c & 7) * 8;
+    }
     auto load_a = [&](int32_t kt) {
 #pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) {
-            const int c = tid + i * NTHR;
-            const int32_t row = row0 + (c >> 3);
-            v4u v = {0u, 0u, 0u, 0u};
-            if (row < T)
-                v = *reinterpret_cast<const v4u *>(x + static_cast<int64_t>(row) * ldx +
-                                                   static_cast<int64_t>(kt) * kPackK + (c & 7) * 8);
-            areg[i] = v;
-        }
+        for (int i = 0; i < A_LOADS; ++i)
+            areg[i] = *reinterpret_cast<const v4u *>(arow[i] + static_cast<int64_t>(kt) * kPackK);
     };
     auto store_a = [&](int buf) {
 #pragma unroll
@@ -176,13 +187,11 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
         for (int nt = 0; nt < NT; ++nt)
             b[nt] = wp[(static_cast<int64_t>(my_tile[nt]) * k_tiles + kt) * 64 + lane];
     };
-    auto load_s = [&](int32_t kt, v2h (&s)[NT]) {
+    auto load_s = [&](int32_t kt, uint16_t (&s)[NT]) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const _Float16 v = __builtin_bit_cast(
-                _Float16, sT[static_cast<int64_t>(kt / 2) * n_pad + my_tile[nt] * kPackN + l32]);
-            s[nt] = v2h{v, v};
-        }
+        for (int nt = 0; nt < NT; ++nt)
+            s[nt] = __builtin_bit_cast(
+                uint16_t, sT[static_cast<int64_t>(kt / 2) * n_pad + my_tile[nt] * kPackN + l32]);
     };
 
     v16f acc[MT][NT];
@@ -193,54 +202,77 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
 
-    v4u bcur[NT], bnext[NT];
-    v2h scur[NT], snext[NT];
+    const uint32_t mask = 0x000F000Fu;
+    uint32_t magic = 0x64006400u;
+    asm volatile("" : "+v"(magic));           // keep it in a VGPR (third operand of v_and_or_b32)
+
+    // One 64-channel step on LDS buffer `buf` with weights b and scales s.
+    auto compute = [&](int buf, const v4u (&b)[NT], const uint16_t (&s)[NT]) {
+        const uint8_t *abase = smem + buf * A_BUF + (wm * MT * 32 + l32) * kAPitch + g * 64;
+        v2h s2[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const _Float16 v = __builtin_bit_cast(_Float16, s[nt]);
+            s2[nt] = v2h{v, v};
+        }
+        // The weights of MFMA step st + 1 are dequantised ahead of the MFMAs of step st, so
+        // that the scheduler has independent VALU work to place between them.
+        v8h bfr[2][NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            bfr[0][nt] = __builtin_bit_cast(v8h, dequant8(b[nt][0], s2[nt], mask, magic));
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            if (st < 3) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    bfr[(st + 1) & 1][nt] =
+                        __builtin_bit_cast(v8h, dequant8(b[nt][st + 1], s2[nt], mask, magic));
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const v8h afr = *reinterpret_cast<const v8h *>(abase + mt * 32 * kAPitch + st * 16);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr, bfr[st & 1][nt], acc[mt][nt], 0, 0, 0);
+            }
+        }
+    };
+
+    // Two steps per trip (K % 128 == 0) with two register sets for the weights, so that no
+    // set is copied and every wait is for loads issued a whole step earlier.  The group
+    // scale changes once per trip.  The last trip fetches the final tile once more
+    // instead of branching; those loads are not used.
+    v4u b0[NT], b1[NT];
+    uint16_t scur[NT], snext[NT];
     load_a(0);
-    load_b(0, bcur);
+    load_b(0, b0);
     load_s(0, scur);
     store_a(0);
     __syncthreads();
 
-    for (int32_t kt = 0; kt < k_tiles; ++kt) {
-        const bool more = kt + 1 < k_tiles;
-        if (more) {
-            load_a(kt + 1);
-            load_b(kt + 1, bnext);
-            if (((kt + 1) & 1) == 0) {                 // a new group of 128 channels starts
-                load_s(kt + 1, snext);
-            } else {
+    // The scheduling fences keep the fetches of the next step ahead of this step's
+    // arithmetic (the compiler would otherwise sink them next to their LDS stores and
+    // expose the whole memory latency).
+    for (int32_t kt = 0; kt < k_tiles; kt += 2) {
+        load_a(kt + 1);
+        load_b(kt + 1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(0, b0, scur);
+        __builtin_amdgcn_sched_barrier(0);
+        store_a(1);
+        __syncthreads();
+
+        const int32_t nx = kt + 2 < k_tiles ? kt + 2 : k_tiles - 1;
+        load_a(nx);
+        load_b(nx, b0);
+        load_s(nx, snext);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(1, b1, scur);
+        __builtin_amdgcn_sched_barrier(0);
+        store_a(0);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) snext[nt] = scur[nt];
-            }
-        }
-        const uint8_t *abase =
-            smem + (kt & 1) * A_BUF + (wm * MT * 32 + l32) * kAPitch + g * 64;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            v8h bfr[NT];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                uint32_t d[4];
-                dequant8(bcur[nt][s], scur[nt], d);
-                const v4u packed = {d[0], d[1], d[2], d[3]};
-                bfr[nt] = __builtin_bit_cast(v8h, packed);
-            }
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const v8h afr = *reinterpret_cast<const v8h *>(abase + mt * 32 * kAPitch + s * 16);
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr, bfr[nt], acc[mt][nt], 0, 0, 0);
-            }
-        }
-        if (more) {
-            store_a((kt + 1) & 1);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                bcur[nt] = bnext[nt];
-                scur[nt] = snext[nt];
-            }
-        }
+        for (int nt = 0; nt < NT; ++nt) scur[nt] = snext[nt];
         __syncthreads();
     }
 
@@ -355,9 +387,10 @@ extern "C" int mquant_w4g128_gemm(const void *x, int64_t ldx, const uint8_t *wp,
     const __half *xh = static_cast<const __half *>(x);
     __half *yh = static_cast<__half *>(y);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // Few tokens: narrow tiles so that the weight stream is spread over all CUs.
-    if (T <= 64) return launch_g128<64, 128, 2, 4>(xh, ldx, wp, yh, ldy, T, N, K, st);
-    const int64_t big = ceil_div(T, 256) * ceil_div(N, 256);
-    if (big >= 192) return launch_g128<256, 256, 2, 4>(xh, ldx, wp, yh, ldy, T, N, K, st);
-    return launch_g128<128, 128, 2, 4>(xh, ldx, wp, yh, ldy, T, N, K, st);
+    // Every wave owns 32 output channels of the tile (WM = 1): a weight is dequantised once
+    // per work-group.  128 x 256 was the fastest tile on all four projection shapes of the
+    // 7B model at T = 1280; few tokens take narrow tiles so that the weight stream is
+    // spread over all CUs.
+    if (T <= 64) return launch_g128<64, 128, 1, 4>(xh, ldx, wp, yh, ldy, T, N, K, st);
+    return launch_g128<128, 256, 1, 8>(xh, ldx, wp, yh, ldy, T, N, K, st);
 }

@@ -71,10 +71,10 @@ def test_dequantised_weight_bit_exact_through_one_hot_rows(mq):
 
 
 @pytest.mark.parametrize("T,N,K", [
-    (1, 32, 128), (5, 200, 256), (64, 136, 384),           # narrow tiles
-    (65, 264, 512), (130, 300, 256),                        # 128x128; N % 8 != 0 -> 2-byte stores
+    (1, 32, 128), (5, 200, 256), (64, 136, 384),           # T <= 64: 64x128 tiles
+    (65, 264, 512), (130, 300, 256),                        # 128x256 tiles; N % 8 != 0 -> 2-byte stores
     (257, 1000, 640), (300, 520, 1024),
-    (1100, 6200, 256),                                      # enough tiles for 256x256, ragged both ways
+    (1100, 6200, 256),                                      # many tiles, ragged both ways
 ])
 def test_linear_matches_oracle(mq, T, N, K):
     rng = np.random.default_rng(T * 7 + N)
