@@ -125,6 +125,75 @@ def test_device_entry_points_validate_before_launch():
     assert f(None, 512, None, P, P, P, 512, 64, 512, 512, 48, 1.0, 1.0, 512, P, need, None) == mq.ERR_NULL
     assert f(P, 512, None, P, P, P, 512, 64, 512, 512, 48, 1.0, 1.0, 96, P, need, None) == mq.ERR_UNSUPPORTED
     assert f(P, 512, None, P, P, P, 512, 64, 512, 512, 65, 1.0, 1.0, 512, P, need, None) == mq.ERR_BAD_SHAPE
+    # weight-only group-128 linear
+    assert L.mquant_w4g128_prepacked_bytes(64, 256) == 2 * 4 * 1024 + 2 * 64 * 2
+    assert L.mquant_w4g128_prepacked_bytes(33, 256) == 2 * 4 * 1024 + 2 * 64 * 2    # N padded to 32
+    assert L.mquant_w4g128_prepacked_bytes(64, 192) == mq.ERR_UNSUPPORTED
+    assert L.mquant_w4g128_prepacked_bytes(-1, 128) == mq.ERR_BAD_SHAPE
+    assert L.mquant_w4g128_prepack(None, P, P, 32, 128, None) == mq.ERR_NULL
+    assert L.mquant_w4g128_prepack(P, None, P, 32, 128, None) == mq.ERR_NULL
+    assert L.mquant_w4g128_prepack(P, P, P + 8, 32, 128, None) == mq.ERR_ALIGNMENT
+    assert L.mquant_w4g128_prepack(P, P, P, 32, 64, None) == mq.ERR_UNSUPPORTED
+    assert L.mquant_w4g128_prepack(None, None, None, 0, 128, None) == mq.OK
+    wo = L.mquant_w4g128_gemm
+    assert wo(None, 256, P, P, 64, 4, 64, 256, None) == mq.ERR_NULL
+    assert wo(P, 128, P, P, 64, 4, 64, 256, None) == mq.ERR_BAD_SHAPE               # ldx < K
+    assert wo(P, 256, P, P, 32, 4, 64, 256, None) == mq.ERR_BAD_SHAPE               # ldy < N
+    assert wo(P, 256, P, P, 64, 4, 64, 192, None) == mq.ERR_UNSUPPORTED             # K % 128
+    assert wo(P, 260, P, P, 64, 4, 64, 256, None) == mq.ERR_ALIGNMENT               # ldx % 8
+    assert wo(P + 2, 256, P, P, 64, 4, 64, 256, None) == mq.ERR_ALIGNMENT
+    assert wo(None, 256, None, None, 64, 0, 64, 256, None) == mq.OK                 # T == 0
+
+
+def test_widened_entry_points_validate_before_launch():
+    """Same for the entry points beyond the W4A8 linear: rejected on the host, nothing launched."""
+    P = 0x1000
+    L = mq.lib
+    qb = L.mquant_hadamard_quant_act_bits
+    assert qb(P, 512, None, P, 4, 512, 2, 1.0, 1.0, 512, 9, None) == mq.ERR_UNSUPPORTED   # bits > 8
+    assert qb(P, 512, None, P, 4, 512, 2, 1.0, 1.0, 512, 1, None) == mq.ERR_UNSUPPORTED   # bits < 2
+    assert qb(None, 512, None, P, 4, 512, 2, 1.0, 1.0, 512, 4, None) == mq.ERR_NULL
+    dq = L.mquant_hadamard_dynquant_act
+    assert dq(P, 512, None, P, None, 4, 512, 512, None) == mq.ERR_NULL                    # no scale output
+    assert dq(P, 256, None, P, P, 4, 512, 512, None) == mq.ERR_BAD_SHAPE
+    assert dq(P, 512, None, P, P, 4, 512, 96, None) == mq.ERR_UNSUPPORTED
+    assert dq(P, 65536, None, P, P, 4, 65536, 512, None) == mq.ERR_UNSUPPORTED            # row too long
+    assert dq(None, 512, None, None, None, 0, 512, 512, None) == mq.OK
+    rs = L.mquant_w4a8_gemm_rowscale
+    assert rs(P, P, P, None, P, 512, None, 4, 512, 512, None, 0, None) == mq.ERR_NULL
+    assert rs(P, P, P, P, P, 256, None, 4, 512, 512, None, 0, None) == mq.ERR_BAD_SHAPE
+    assert rs(P, P, P, P + 2, P, 512, None, 4, 512, 512, None, 0, None) == mq.ERR_ALIGNMENT
+    idx = (ctypes.c_int32 * 2)(0, 512)
+    idx_out = (ctypes.c_int32 * 2)(0, 5120)
+    sc = (ctypes.c_float * 2)(0.1, 0.2)
+    sc_nan = (ctypes.c_float * 2)(0.1, float("nan"))
+    rms = L.mquant_w4a8_gemm_rms
+    assert rms(P, P, P, P, 512, None, 4, 512, 1024, 0, 1.0, 1.0, idx, None, sc, 2, None, 0, None) == mq.ERR_NULL
+    assert rms(P, P, P, P, 512, None, 4, 512, 1024, 0, 1.0, 1.0, idx_out, P, sc, 2, None, 0, None) == mq.ERR_BAD_SHAPE
+    assert rms(P, P, P, P, 512, None, 4, 512, 1024, 0, 1.0, 1.0, idx, P, sc_nan, 2, None, 0, None) == mq.ERR_BAD_SHAPE
+    assert rms(P, P, P, P, 512, None, 4, 512, 1024, 0, 1.0, 1.0, idx, P, sc, 65, None, 0, None) == mq.ERR_BAD_SHAPE
+    assert rms(P, P, P, P, 512, None, 4, 512, 1024, 0, 1.0, 1.0, idx, P, sc, -1, None, 0, None) == mq.ERR_BAD_SHAPE
+    dec = L.mquant_w4a8_linear_decode
+    assert dec(P, 512, P, P, P, 512, 5, 512, 512, 0, 1.0, 1.0, 512, None) == mq.ERR_UNSUPPORTED   # T > 4
+    assert dec(P, 512, P, P, P, 512, 1, 512, 512, 0, 1.0, 1.0, 256, None) == mq.ERR_UNSUPPORTED   # block size
+    assert dec(None, 512, P, P, P, 512, 1, 512, 512, 0, 1.0, 1.0, 512, None) == mq.ERR_NULL
+    assert dec(P, 512, P, P, P, 512, 1, 512, 512, 2, 1.0, 1.0, 512, None) == mq.ERR_BAD_SHAPE     # n_vis > T
+    assert dec(None, 512, None, None, None, 512, 0, 512, 512, 0, 1.0, 1.0, 512, None) == mq.OK
+    rope = L.mquant_rope_apply
+    assert rope(None, 1024, P, 4, 8, 128, 10000.0, None) == mq.ERR_NULL
+    assert rope(P, 1024, P, 4, 8, 96, 10000.0, None) == mq.ERR_UNSUPPORTED                # head_dim
+    assert rope(P, 512, P, 4, 8, 128, 10000.0, None) == mq.ERR_BAD_SHAPE                  # ldx < heads * dim
+    assert rope(P, 1024, P, 4, 8, 128, 0.0, None) == mq.ERR_BAD_SHAPE
+    assert rope(None, 1024, None, 0, 8, 128, 10000.0, None) == mq.OK
+    att = L.mquant_aifs_attention
+    need = L.mquant_aifs_attention_workspace_bytes(64, 4, 128)
+    assert need >= 64 * 4 * 128 * 2
+    assert att(P, 3584, P, 512, P, 512, P, 3584, P, 64, 28, 4, 128, P, need - 1, None) == mq.ERR_WORKSPACE
+    assert att(P, 3584, P, 512, P, 512, P, 3584, P, 64, 28, 4, 64, P, need, None) == mq.ERR_UNSUPPORTED
+    assert att(P, 3584, P, 512, P, 512, P, 3584, P, 64, 28, 5, 128, P, need, None) == mq.ERR_BAD_SHAPE   # 28 % 5
+    assert att(None, 3584, P, 512, P, 512, P, 3584, P, 64, 28, 4, 128, P, need, None) == mq.ERR_NULL
+    assert att(P, 3580, P, 512, P, 512, P, 3584, P, 64, 28, 4, 128, P, need, None) == mq.ERR_BAD_SHAPE   # ldq < heads * dim
+    assert att(None, 3584, None, 512, None, 512, None, 3584, None, 0, 28, 4, 128, None, 0, None) == mq.OK
 
 
 def test_static_scale_host_formula_matches_oracle():
