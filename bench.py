@@ -428,6 +428,38 @@ def bench_weight_only(args, torch, mq, lin, T, w4a8_gemm_ms):
         del wp
     out["us_per_step"] = round(total_us, 2)
     out["TFLOPs"] = round(flops / total_us / 1e6, 1)
+    # decode shape: the same four weight matrices against one token (weight-streaming GEMV)
+    dec, dec_us, dec_bytes = {}, 0.0, 0.0
+    for proj, l in lin.items():
+        K, N = l["K"], l["N"]
+        wq = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device="cuda", generator=gen)
+        sc = (torch.rand((N, K // 128), device="cuda", generator=gen) * 0.008 + 0.002).to(torch.float16)
+        wp = mq.w4g128_prepack(wq, sc)
+        del wq
+        x1 = l["x"][:1]
+        y1 = l["y"][:1]
+        fn = lambda: mq.w4g128_gemm(x1, wp, N, out=y1)
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                fn()
+            e1.record()
+            e1.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 50.0)
+        nbytes = float(wp.numel()) + 2.0 * K + 2.0 * N
+        dec[proj] = {"us": round(best, 2), "GBps": round(nbytes / best / 1e3, 1)}
+        dec_us += best
+        dec_bytes += nbytes
+        del wp
+    out["decode_T1"] = {"per_projection": dec, "us_per_layer": round(dec_us, 2),
+                        "GBps": round(dec_bytes / dec_us / 1e3, 1),
+                        "frac_of_hbm_peak": round(dec_bytes / dec_us / 1e3 / HBM_PEAK_GBPS, 4)}
     out["frac_of_fp16_mfma_peak"] = round(flops / total_us / 1e6 / FP16_MFMA_PEAK_TFLOPS, 4)
     out["w4a8_gemm_us_per_step"] = round(sum(w4a8_gemm_ms.values()) * 1e3, 2)
     return out

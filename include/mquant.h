@@ -378,8 +378,10 @@ int mquant_w4g128_prepack(const uint8_t *w_canonical_dev, const void *scales_dev
  *   w_prepacked_dev : output of mquant_w4g128_prepack for the same (N, K)
  *   y_dev : fp16 [T, ldy] (written: columns 0..N-1 of every row), ldy >= N; 16-byte
  *           stores are used when N % 8 == 0, ldy % 8 == 0 and y_dev is 16-byte aligned
- * The summation order is the matrix core's and is not specified; results agree with
- * a double-precision sum to within fp32 accumulation error plus the final fp16 rounding.
+ * Few tokens (decode) are routed to a weight-streaming GEMV kernel, many to the MFMA
+ * GEMM.  The summation order is the matrix core's (and, in the GEMV, fixed across the
+ * waves that split K) and is not specified; results agree with a double-precision sum
+ * to within fp32 accumulation error plus the final fp16 rounding.
  * T == 0 or N == 0 is a no-op.  Errors: ERR_BAD_SHAPE, ERR_UNSUPPORTED (K % 128 != 0 or
  * K == 0), ERR_NULL, ERR_ALIGNMENT, ERR_HIP.
  */

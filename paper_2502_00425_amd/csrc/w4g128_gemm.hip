@@ -327,6 +327,97 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
     }
 }
 
+// Decode shape (T <= 32): the weights are streamed once and nothing is reused.  One
+// work-group owns one 32-channel tile, its NWAVES waves split K, and every wave requests
+// a batch of KT k-tiles (activation fragments first, they hit L2; then the weights, with
+// the non-temporal hint, and their scales) before it touches the first one.  Loads are
+// branch free: k-tiles past a wave's range are clamped and their weights replaced by
+// code 0, lanes whose token row is >= T read row T - 1 (rows >= T of the MFMA result
+// are never stored).  The fp32 partial sums of the waves meet in LDS and are added in
+// wave order.
+template <int NWAVES, int KT>
+__global__ __launch_bounds__(NWAVES * 64) void w4g128_gemv_kernel(
+    const __half *__restrict__ x, int64_t ldx, const v4u *__restrict__ wp,
+    const __half *__restrict__ sT, __half *__restrict__ y, int64_t ldy, int32_t T, int32_t N,
+    int32_t K, int32_t n_pad)
+{
+    __shared__ float red[NWAVES][16][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int32_t ntile = blockIdx.x;
+    const int32_t k_tiles = K / kPackK;
+    const int32_t per_wave = (k_tiles + NWAVES - 1) / NWAVES;
+    const int32_t kt_begin = wave * per_wave;
+    int32_t kt_end = kt_begin + per_wave;
+    kt_end = kt_end < k_tiles ? kt_end : k_tiles;
+    const int32_t n = ntile * kPackN + l32;
+
+    v16f acc0, acc1;                                      // two chains: no back-to-back dependent MFMAs
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        acc0[r] = 0.0f;
+        acc1[r] = 0.0f;
+    }
+    const v4u *wtile = wp + static_cast<int64_t>(ntile) * k_tiles * 64 + lane;
+    const __half *xrow = x + static_cast<int64_t>(l32 < T ? l32 : T - 1) * ldx + g * 32;
+    const __half *scol = sT + ntile * kPackN + l32;
+    const uint32_t mask = 0x000F000Fu;
+    uint32_t magic = 0x64006400u;
+    asm volatile("" : "+v"(magic));
+
+    for (int32_t base = kt_begin; base < kt_end; base += KT) {
+        v4u a[KT][4], b[KT];
+        uint16_t sc[KT];
+#pragma unroll
+        for (int u = 0; u < KT; ++u) {
+            int32_t kt = base + u;
+            kt = kt < kt_end ? kt : kt_end - 1;
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+                a[u][st] = *reinterpret_cast<const v4u *>(xrow + kt * kPackK + st * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < KT; ++u) {
+            int32_t kt = base + u;
+            kt = kt < kt_end ? kt : kt_end - 1;
+            b[u] = __builtin_nontemporal_load(wtile + static_cast<int64_t>(kt) * 64);
+            sc[u] = __builtin_bit_cast(uint16_t, scol[static_cast<int64_t>(kt / 2) * n_pad]);
+        }
+#pragma unroll
+        for (int u = 0; u < KT; ++u) {
+            const bool live = base + u < kt_end;                     // wave-uniform
+            const _Float16 sv = __builtin_bit_cast(_Float16, sc[u]);
+            const v2h s2 = {sv, sv};
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                const uint32_t code = live ? b[u][st] : 0x88888888u;
+                const v8h bf = __builtin_bit_cast(v8h, dequant8(code, s2, mask, magic));
+                const v8h af = __builtin_bit_cast(v8h, a[u][st]);
+                if (st & 1) acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf, acc1, 0, 0, 0);
+                else acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf, acc0, 0, 0, 0);
+            }
+        }
+        // all memory reads of the batch first, then the arithmetic
+        __builtin_amdgcn_sched_group_barrier(0x020, 6 * KT, 0);
+        __builtin_amdgcn_sched_group_barrier(0x00A, 20 * 4 * KT, 0);
+    }
+
+    const int rmax = T <= 8 ? 4 : (T <= 16 ? 8 : 16);     // accumulator registers that can hold a row < T
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        if (r < rmax) red[wave][r][lane] = acc0[r] + acc1[r];
+    __syncthreads();
+    for (int r = wave; r < rmax; r += NWAVES) {
+        const int32_t row = acc_row(r, g);
+        if (row < T && n < N) {
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < NWAVES; ++w) sum += red[w][r][lane];
+            y[static_cast<int64_t>(row) * ldy + n] = __float2half_rn(sum);
+        }
+    }
+}
+
 template <int BM, int BN, int WM, int WN>
 int launch_g128(const __half *x, int64_t ldx, const uint8_t *wp, __half *y, int64_t ldy, int32_t T,
                 int32_t N, int32_t K, hipStream_t stream)
@@ -387,10 +478,37 @@ extern "C" int mquant_w4g128_gemm(const void *x, int64_t ldx, const uint8_t *wp,
     const __half *xh = static_cast<const __half *>(x);
     __half *yh = static_cast<__half *>(y);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // Every wave owns 32 output channels of the tile (WM = 1): a weight is dequantised once
+    // Decode shapes stream the weights through the GEMV.  In the GEMM every wave owns 32
+    // output channels of the tile (WM = 1): a weight is dequantised once
     // per work-group.  128 x 256 was the fastest tile on all four projection shapes of the
-    // 7B model at T = 1280; few tokens take narrow tiles so that the weight stream is
-    // spread over all CUs.
+    // 7B model at T = 1280.
+    const int32_t n_tiles32 = static_cast<int32_t>(ceil_div(N, kPackN));
+    if (T <= 32 || (T <= 64 && n_tiles32 < 512)) {
+        const int64_t w_bytes = static_cast<int64_t>(n_tiles32) * (K / kPackK) * kPackTileBytes;
+        const __half *sT = reinterpret_cast<const __half *>(wp + w_bytes);
+        const v4u *wt = reinterpret_cast<const v4u *>(wp);
+        const int32_t n_pad = n_tiles32 * kPackN;
+        // The GEMV holds 32 token rows (one MFMA M extent).  With few output tiles, up to 64
+        // rows take two launches: that still beats a GEMM whose few tiles would each walk all
+        // of K alone (18944 x 3584 at T = 64: 91 us against 129 us).
+        for (int32_t t0 = 0; t0 < T; t0 += 32) {
+            const int32_t tc = T - t0 < 32 ? T - t0 : 32;
+            const __half *xc = xh + static_cast<int64_t>(t0) * ldx;
+            __half *yc = yh + static_cast<int64_t>(t0) * ldy;
+            // Many tiles: small work-groups with one k-tile in flight per wave keep the register
+            // count low and several groups resident per CU (fastest on 1184 tiles x 56 k-tiles);
+            // few tiles: sixteen waves split K.
+            if (n_tiles32 >= 512)
+                MQ_LAUNCH((w4g128_gemv_kernel<8, 1>), dim3(n_tiles32), dim3(512), 0, st, xc, ldx, wt,
+                          sT, yc, ldy, tc, N, K, n_pad);
+            else
+                MQ_LAUNCH((w4g128_gemv_kernel<16, 2>), dim3(n_tiles32), dim3(1024), 0, st, xc, ldx,
+                          wt, sT, yc, ldy, tc, N, K, n_pad);
+            const int status = launch_status();
+            if (status != MQUANT_OK) return status;
+        }
+        return MQUANT_OK;
+    }
     if (T <= 64) return launch_g128<64, 128, 1, 4>(xh, ldx, wp, yh, ldy, T, N, K, st);
     return launch_g128<128, 256, 1, 8>(xh, ldx, wp, yh, ldy, T, N, K, st);
 }

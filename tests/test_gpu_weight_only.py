@@ -71,7 +71,9 @@ def test_dequantised_weight_bit_exact_through_one_hot_rows(mq):
 
 
 @pytest.mark.parametrize("T,N,K", [
-    (1, 32, 128), (5, 200, 256), (64, 136, 384),           # T <= 64: 64x128 tiles
+    (1, 32, 128), (5, 200, 256), (9, 72, 1152), (16, 200, 640), (31, 40, 2176), (32, 136, 384),   # GEMV
+    (33, 64, 128), (64, 136, 384),                          # two GEMV launches
+    (50, 16400, 128),                                       # 64x128 GEMM tiles (many channels)
     (65, 264, 512), (130, 300, 256),                        # 128x256 tiles; N % 8 != 0 -> 2-byte stores
     (257, 1000, 640), (300, 520, 1024),
     (1100, 6200, 256),                                      # many tiles, ragged both ways
