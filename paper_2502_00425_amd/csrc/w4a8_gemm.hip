@@ -25,6 +25,8 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "hadamard_segment.h"
 #include "mquant_internal.h"
 
@@ -911,13 +913,14 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
     // read by one XCD only), else equal bands of about six rows.
     const int32_t band = tiles_m <= 8 ? tiles_m
                                       : static_cast<int32_t>(ceil_div(tiles_m, ceil_div(tiles_m, 6)));
-    static bool attr_set = false;       // raising the dynamic LDS limit is idempotent
-    if (!attr_set) {
+    // Raising the dynamic LDS limit is idempotent: threads racing here at most repeat it.
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 static_cast<int>(lds)) != hipSuccess)
             return MQUANT_ERR_HIP;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     MQ_LAUNCH(kern, dim3(tiles_m * tiles_n * splits), dim3(WM * WN * 64), lds, stream, xq,
                        reinterpret_cast<const uint4 *>(wp), static_cast<const __half *>(w_scale),
@@ -1168,17 +1171,25 @@ int launch_decode_fused(const __half *x, int64_t ldx, const uint4 *wp, const __h
     if (n_tiles >= 256) {
         const size_t lds = static_cast<size_t>(xq_bytes > 8 * 4096 ? xq_bytes : 8 * 4096);
         auto kern = w4a8_decode_fused_kernel<8, 4, B>;
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return MQUANT_ERR_HIP;
+        static std::atomic<bool> attr_set{false};
+        if (!attr_set.load(std::memory_order_acquire)) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+                return MQUANT_ERR_HIP;
+            attr_set.store(true, std::memory_order_release);
+        }
         MQ_LAUNCH(kern, dim3(n_tiles), dim3(512), lds, stream, x, ldx, wp, w_scale, y, ldy, T, N, K, ep,
                   c_vis, c_txt);
     } else {
         const size_t lds = static_cast<size_t>(xq_bytes > 16 * 4096 ? xq_bytes : 16 * 4096);
         auto kern = w4a8_decode_fused_kernel<16, 4, B>;
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return MQUANT_ERR_HIP;
+        static std::atomic<bool> attr_set{false};
+        if (!attr_set.load(std::memory_order_acquire)) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+                return MQUANT_ERR_HIP;
+            attr_set.store(true, std::memory_order_release);
+        }
         MQ_LAUNCH(kern, dim3(n_tiles), dim3(1024), lds, stream, x, ldx, wp, w_scale, y, ldy, T, N, K, ep,
                   c_vis, c_txt);
     }

@@ -26,6 +26,8 @@
 // so that the 32 lanes of a tile read consecutive halves.
 #include <hip/hip_fp16.h>
 
+#include <atomic>
+
 #include "mquant_internal.h"
 
 using namespace mquant;
@@ -38,10 +40,10 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr int kGroup = 128;               // input channels per weight scale
-constexpr int kAPitch = 144;              // bytes per LDS row of the A tile: 64 halves + 16 pad
+constexpr int kAPitch = 272;              // bytes per LDS row of the A tile: 128 halves + 16 pad
 
-// 16-byte reads of 16 consecutive rows at pitch 144 B start at banks 36 r mod 64 =
-// {0,36,8,44,16,52,24,60,32,4,40,12,48,20,56,28}: the 64 banks exactly once.
+// 16-byte reads of 16 consecutive rows at pitch 272 B start at banks 68 r mod 64 = 4 r:
+// the 64 banks exactly once.
 
 __global__ __launch_bounds__(256) void g128_prepack_kernel(
     const uint8_t *__restrict__ w, const __half *__restrict__ scales, uint32_t *__restrict__ out_w,
@@ -124,9 +126,10 @@ __device__ __forceinline__ void tile_of_group(int32_t id, int32_t tiles_m, int32
     tn = in_band / rows;
 }
 
-// Work-group tile BM x BN, WM x WN wavefronts.  K advances 64 channels at a time;
-// the A tile of the next step is fetched into registers while the current one is
-// multiplied, then written to the other LDS buffer: one barrier per step.
+// Work-group tile BM x BN, WM x WN wavefronts.  K advances one scale group (128
+// channels, two k-tiles) at a time; the A tile of the next group is fetched into
+// registers while the current one is multiplied, then written to the other LDS
+// buffer: one barrier per group.
 template <int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
     const __half *__restrict__ x, int64_t ldx, const v4u *__restrict__ wp,
@@ -137,11 +140,9 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
     constexpr int NW = WM * WN, NTHR = NW * 64;
     constexpr int MT = BM / WM / 32, NT = BN / WN / 32;
     constexpr int A_BUF = BM * kAPitch;
-    constexpr int A_LOADS = BM * 8 / NTHR;            // 16-byte chunks of the A tile per thread
-    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && (BM * 8) % NTHR == 0, "tile shape");
-    constexpr int PATCH = NW * 32 * (NT * 64 + 16);  // epilogue patches, one per wave
-    constexpr int SMEM = 2 * A_BUF > PATCH ? 2 * A_BUF : PATCH;
-    __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM];
+    constexpr int A_LOADS = BM * 16 / NTHR;           // 16-byte chunks of the A tile per thread
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && (BM * 16) % NTHR == 0, "tile shape");
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];   // g128_lds_bytes<...>()
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
@@ -151,6 +152,7 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
     const int32_t row0 = tm * BM;
     const int32_t ntile0 = tn * (BN / 32);
     const int32_t k_tiles = K / kPackK;
+    const int32_t trips = K / kGroup;
     const int32_t n_pad = n_tiles32 * kPackN;
 
     // n-tiles of this wave, clamped to the last real tile (columns beyond N are never stored)
@@ -167,31 +169,33 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) {
         const int c = tid + i * NTHR;
-        const int32_t row = row0 + (c >> 3);
-        arow[i] = x + static_cast<int64_t>(row < T ? row : T - 1) * ldx + (c & 7) * 8;
+        const int32_t row = row0 + (c >> 4);
+        arow[i] = x + static_cast<int64_t>(row < T ? row : T - 1) * ldx + (c & 15) * 8;
     }
-    auto load_a = [&](int32_t kt) {
+    auto load_a = [&](int32_t trip) {
 #pragma unroll
         for (int i = 0; i < A_LOADS; ++i)
-            areg[i] = *reinterpret_cast<const v4u *>(arow[i] + static_cast<int64_t>(kt) * kPackK);
+            areg[i] = *reinterpret_cast<const v4u *>(arow[i] + static_cast<int64_t>(trip) * kGroup);
     };
     auto store_a = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < A_LOADS; ++i) {
             const int c = tid + i * NTHR;
-            *reinterpret_cast<v4u *>(smem + buf * A_BUF + (c >> 3) * kAPitch + (c & 7) * 16) = areg[i];
+            *reinterpret_cast<v4u *>(smem + buf * A_BUF + (c >> 4) * kAPitch + (c & 15) * 16) = areg[i];
         }
     };
-    auto load_b = [&](int32_t kt, v4u (&b)[NT]) {
+    auto load_b = [&](int32_t trip, v4u (&b)[2][NT]) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            b[nt] = wp[(static_cast<int64_t>(my_tile[nt]) * k_tiles + kt) * 64 + lane];
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                b[kk][nt] = wp[(static_cast<int64_t>(my_tile[nt]) * k_tiles + 2 * trip + kk) * 64 + lane];
     };
-    auto load_s = [&](int32_t kt, uint16_t (&s)[NT]) {
+    auto load_s = [&](int32_t trip, uint16_t (&s)[NT]) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
             s[nt] = __builtin_bit_cast(
-                uint16_t, sT[static_cast<int64_t>(kt / 2) * n_pad + my_tile[nt] * kPackN + l32]);
+                uint16_t, sT[static_cast<int64_t>(trip) * n_pad + my_tile[nt] * kPackN + l32]);
     };
 
     v16f acc[MT][NT];
@@ -206,8 +210,8 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
     uint32_t magic = 0x64006400u;
     asm volatile("" : "+v"(magic));           // keep it in a VGPR (third operand of v_and_or_b32)
 
-    // One 64-channel step on LDS buffer `buf` with weights b and scales s.
-    auto compute = [&](int buf, const v4u (&b)[NT], const uint16_t (&s)[NT]) {
+    // One scale group (eight MFMA steps) on LDS buffer `buf` with weights b and scales s.
+    auto compute = [&](int buf, const v4u (&b)[2][NT], const uint16_t (&s)[NT]) {
         const uint8_t *abase = smem + buf * A_BUF + (wm * MT * 32 + l32) * kAPitch + g * 64;
         v2h s2[NT];
 #pragma unroll
@@ -215,64 +219,78 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
             const _Float16 v = __builtin_bit_cast(_Float16, s[nt]);
             s2[nt] = v2h{v, v};
         }
-        // The weights of MFMA step st + 1 are dequantised ahead of the MFMAs of step st, so
-        // that the scheduler has independent VALU work to place between them.
-        v8h bfr[2][NT];
+        // Operands of MFMA step i + 1 (A fragments from LDS, dequantised weights) are produced
+        // while the MFMAs of step i run: a fragment read just before its MFMA would expose
+        // the LDS latency once per MFMA.
+        v8h bfr[2][NT], afr[2][MT];
+        auto fetch = [&](int i) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            bfr[0][nt] = __builtin_bit_cast(v8h, dequant8(b[nt][0], s2[nt], mask, magic));
+            for (int mt = 0; mt < MT; ++mt)
+                afr[i & 1][mt] = *reinterpret_cast<const v8h *>(abase + mt * 32 * kAPitch +
+                                                                (i >> 2) * 128 + (i & 3) * 16);
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            if (st < 3) {
+            for (int nt = 0; nt < NT; ++nt)
+                bfr[i & 1][nt] =
+                    __builtin_bit_cast(v8h, dequant8(b[i >> 2][nt][i & 3], s2[nt], mask, magic));
+        };
+        fetch(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (i < 7) fetch(i + 1);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    bfr[(st + 1) & 1][nt] =
-                        __builtin_bit_cast(v8h, dequant8(b[nt][st + 1], s2[nt], mask, magic));
-            }
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[i & 1][mt], bfr[i & 1][nt],
+                                                                        acc[mt][nt], 0, 0, 0);
+            // order inside the step: the next step's fragment reads first, then its VALU work
+            // dealt between this step's MFMAs
+            if (i < 7) {
+                __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const v8h afr = *reinterpret_cast<const v8h *>(abase + mt * 32 * kAPitch + st * 16);
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr, bfr[st & 1][nt], acc[mt][nt], 0, 0, 0);
+                for (int j = 0; j < MT * NT; ++j) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, (16 * NT + MT * NT - 1) / (MT * NT), 0);
+                }
             }
+            __builtin_amdgcn_sched_barrier(0);      // nothing moves across steps: bounds the live operands
         }
     };
 
-    // Two steps per trip (K % 128 == 0) with two register sets for the weights, so that no
-    // set is copied and every wait is for loads issued a whole step earlier.  The group
-    // scale changes once per trip.  The last trip fetches the final tile once more
-    // instead of branching; those loads are not used.
-    v4u b0[NT], b1[NT];
-    uint16_t scur[NT], snext[NT];
+    // Two groups per loop trip with two register sets for the weights, so that no set is
+    // copied and every wait is for loads issued a whole group earlier.  The last fetch of
+    // a tile repeats the final group instead of branching; it is not used.  The scheduling
+    // fences keep the fetches of the next group ahead of this group's arithmetic (the
+    // compiler would otherwise sink them next to their LDS stores and expose the whole
+    // memory latency).
+    v4u b0[2][NT], b1[2][NT];
+    uint16_t s0[NT], s1[NT];
     load_a(0);
     load_b(0, b0);
-    load_s(0, scur);
+    load_s(0, s0);
     store_a(0);
     __syncthreads();
 
-    // The scheduling fences keep the fetches of the next step ahead of this step's
-    // arithmetic (the compiler would otherwise sink them next to their LDS stores and
-    // expose the whole memory latency).
-    for (int32_t kt = 0; kt < k_tiles; kt += 2) {
-        load_a(kt + 1);
-        load_b(kt + 1, b1);
+    for (int32_t t = 0; t < trips; t += 2) {
+        const int32_t t1 = t + 1 < trips ? t + 1 : trips - 1;
+        load_a(t1);
+        load_b(t1, b1);
+        load_s(t1, s1);
         __builtin_amdgcn_sched_barrier(0);
-        compute(0, b0, scur);
+        compute(0, b0, s0);
         __builtin_amdgcn_sched_barrier(0);
         store_a(1);
         __syncthreads();
+        if (t + 1 >= trips) break;
 
-        const int32_t nx = kt + 2 < k_tiles ? kt + 2 : k_tiles - 1;
-        load_a(nx);
-        load_b(nx, b0);
-        load_s(nx, snext);
+        const int32_t t2 = t + 2 < trips ? t + 2 : trips - 1;
+        load_a(t2);
+        load_b(t2, b0);
+        load_s(t2, s0);
         __builtin_amdgcn_sched_barrier(0);
-        compute(1, b1, scur);
+        compute(1, b1, s1);
         __builtin_amdgcn_sched_barrier(0);
         store_a(0);
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) scur[nt] = snext[nt];
         __syncthreads();
     }
 
@@ -302,7 +320,6 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void w4g128_gemm_kernel(
     constexpr int ROWB = NT * 64 + 16;
     constexpr int LPR = NT * 64 / 16;
     constexpr int RPI = 64 / LPR;
-    static_assert(NW * 32 * ROWB == PATCH, "patch size");
     uint8_t *patch = smem + wave * (32 * ROWB);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -419,6 +436,14 @@ __global__ __launch_bounds__(NWAVES * 64) void w4g128_gemv_kernel(
 }
 
 template <int BM, int BN, int WM, int WN>
+constexpr int g128_lds_bytes()
+{
+    constexpr int a = 2 * BM * kAPitch;                                   // two A buffers
+    constexpr int patch = WM * WN * 32 * (BN / WN / 32 * 64 + 16);        // epilogue patches
+    return a > patch ? a : patch;
+}
+
+template <int BM, int BN, int WM, int WN>
 int launch_g128(const __half *x, int64_t ldx, const uint8_t *wp, __half *y, int64_t ldy, int32_t T,
                 int32_t N, int32_t K, hipStream_t stream)
 {
@@ -429,7 +454,17 @@ int launch_g128(const __half *x, int64_t ldx, const uint8_t *wp, __half *y, int6
     const __half *sT = reinterpret_cast<const __half *>(wp + w_bytes);
     const int32_t wide = (N % 8 == 0 && ldy % 8 == 0 && aligned_to(y, 16)) ? 1 : 0;
     const int32_t band = tiles_m < 4 ? tiles_m : 4;
-    MQ_LAUNCH((w4g128_gemm_kernel<BM, BN, WM, WN>), dim3(tiles_m * tiles_n), dim3(WM * WN * 64), 0,
+    constexpr int lds = g128_lds_bytes<BM, BN, WM, WN>();
+    auto kern = w4g128_gemm_kernel<BM, BN, WM, WN>;
+    // Raising the dynamic LDS limit is idempotent: threads racing here at most repeat it.
+    static std::atomic<bool> attr_set{false};
+    if (lds > 64 * 1024 && !attr_set.load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return MQUANT_ERR_HIP;
+        attr_set.store(true, std::memory_order_release);
+    }
+    MQ_LAUNCH(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * 64), lds,
               stream, x, ldx, reinterpret_cast<const v4u *>(wp), sT, y, ldy, T, N, K, tiles_m,
               tiles_n, n_tiles32, wide, band);
     return launch_status();
