@@ -482,3 +482,60 @@ def test_gemm_seeded_shape_sweep(mq):
         check_y(y.cpu().numpy(), ref, f"sweep {(T, N, K)}")
         y2 = mq.w4a8_gemm(dev(xq), mq.w4_prepack(dev(packed)), dev(w_scale), N, V, 0.07, 0.009)
         check_y(y2.cpu().numpy(), ref, f"sweep, no acc_out {(T, N, K)}")
+
+
+def test_prefill_step_as_hip_graph_replays_match_plain_launches(mq):
+    """The benchmark replays a step (mask remap, row permute, rotate+quant and GEMM per linear)
+    from one captured HIP graph.  Every replay must reproduce the plain launches bit for bit,
+    with other work and synchronisations between the replays; shapes cover the GEMV, both GEMM
+    tiles and the split-K path with its workspace."""
+    rng = np.random.default_rng(88)
+    T, B = 300, 64
+    spans = [(10, 120), (200, 60)]
+    perm, _, V = mq.aifs_build_perm(T, spans)
+    permd = dev(perm)
+    mask = torch.tril(torch.ones((T, T), dtype=torch.uint8, device="cuda"))
+    mask_u = torch.empty_like(mask)
+    lins = []
+    for K, N in [(512, 264), (8192, 264), (1024, 2048)]:
+        x = dev((rng.standard_normal((T, K)) * 2).astype(np.float16))
+        wp = mq.w4_prepack(dev(rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)))
+        w_scale = dev(rng.uniform(0.005, 0.02, size=N).astype(np.float16))
+        nws = mq.w4a8_workspace_bytes(T, N, K)
+        lins.append({"x": x, "wp": wp, "w_scale": w_scale, "N": N, "K": K,
+                     "xq": torch.empty((T, K), dtype=torch.int8, device="cuda"),
+                     "y": torch.empty((T, N), dtype=torch.float16, device="cuda"),
+                     "ws": torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None})
+    assert any(l["ws"] is not None for l in lins), "one shape must take the split-K path"
+    x_u = torch.empty_like(lins[0]["x"])
+
+    def step():
+        mq.aifs_remap_mask(mask, permd, out=mask_u)
+        mq.aifs_permute(lins[0]["x"], permd, out=x_u)
+        for l in lins:
+            mq.hadamard_quant_act(l["x"], V, 0.05, 0.02, B, perm_dev=permd, out=l["xq"])
+            mq.w4a8_gemm(l["xq"], l["wp"], l["w_scale"], l["N"], V, 0.05, 0.02, out=l["y"], workspace=l["ws"])
+
+    outputs = lambda: [mask_u.clone(), x_u.clone()] + [l["y"].clone() for l in lins] + [l["xq"].clone() for l in lins]
+    say("graph: plain launches")
+    step()
+    torch.cuda.synchronize()
+    want = outputs()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                                           # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        say(f"graph: replay {rep}")
+        for t in [mask_u, x_u] + [l["y"] for l in lins] + [l["xq"] for l in lins]:
+            t.fill_(3)                                   # eager work of the program between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(outputs(), want):
+            assert torch.equal(a, b), f"replay {rep} differs from the plain launches"
