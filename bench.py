@@ -609,6 +609,19 @@ def bench_decode(args, torch, mq, wl):
                 for proj, (K, N, wp, ws) in layer.items():
                     mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
 
+        def layer_pass():
+            # a decoder layer as deployed: q/k/v and gate/up concatenated, one rotate+quant per
+            # distinct input (four per layer), four GEMVs
+            for layer in fused_layers:
+                for proj, (K, N, wp, ws) in layer.items():
+                    mq.hadamard_quant_act(xs[K], 0, s_txt, s_txt, 512, out=xq[K])
+                    mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
+
+        def layer_one_launch_pass():
+            for layer in fused_layers:
+                for proj, (K, N, wp, ws) in layer.items():
+                    mq.w4a8_linear_decode(xs[K], wp, ws, N, 0, s_txt, s_txt, 512, out=ys[N])
+
         def gemv_streams_pass():
             # Kernel throughput when launches overlap: the GEMVs here have no data dependence
             # on each other (own input and output buffers), so four independent stream chains
@@ -628,9 +641,10 @@ def bench_decode(args, torch, mq, wl):
 
         bytes_layer = sum(K * N / 2 + 2 * N + T * K + 2 * T * N for (K, N) in wd.projections.values())
         res = {}
-        legs = [("quant+gemv", one_pass)]
+        legs = [("quant+gemv", one_pass), ("layer_4quant_4gemv", layer_pass)]
         if T <= 4:
             legs.append(("quant+gemv_one_launch", fused_linear_pass))
+            legs.append(("layer_4_one_launch_linears", layer_one_launch_pass))
         for name, fn in legs + [("gemv_only", gemv_only_pass),
                          ("gemv_only_fused_qkv_gateup", gemv_fused_pass),
                          ("gemv_only_4streams", gemv_streams_pass)]:
