@@ -66,7 +66,7 @@ def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards by rows / output channels, see DESIGN.md)", file=sys.stderr)
+              "(rows and output channels are independent, so the path would shard along either without a collective)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
