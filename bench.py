@@ -41,8 +41,8 @@ GEMM_TRAFFIC_BYTES_PER_LAUNCH = 183.0e6
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--decode-layers", type=int, default=28)
     ap.add_argument("--decode-iters", type=int, default=10)
     ap.add_argument("--no-decode", action="store_true")
