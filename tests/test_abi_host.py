@@ -200,3 +200,16 @@ def test_static_scale_host_formula_matches_oracle():
     import paper_2502_00425_amd as pkg
     for absmax, B in [(1234.5, 512), (7.0, 128), (1e-3, 1), (65504.0 * 512, 512)]:
         assert np.float32(pkg.static_scale_from_absmax(absmax, B)) == orc.static_scale_from_absmax(absmax, B)
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 (and as C++) on its own."""
+    import shutil
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "mquant.h")
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    for cmd in (["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr],
+                ["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr]):
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert r.returncode == 0, r.stdout
