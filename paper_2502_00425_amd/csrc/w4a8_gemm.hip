@@ -255,8 +255,10 @@ __global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_ke
     // With split-K the K range is one more factor of the tile grid (next to tn).
     int32_t tm, tn;
     tile_of_group(blockIdx.x, tiles_m, tiles_n * splits, band, tm, tn);
-    const int32_t split = tn % splits;
-    tn /= splits;
+    // K range outermost: neighbouring columns of the order (the tiles one XCD holds
+    // at a time) then share their A k-range, which its L2 fetches once.
+    const int32_t split = tn / tiles_n;
+    tn -= split * tiles_n;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
