@@ -539,3 +539,26 @@ def test_prefill_step_as_hip_graph_replays_match_plain_launches(mq):
         torch.cuda.synchronize()
         for a, b in zip(outputs(), want):
             assert torch.equal(a, b), f"replay {rep} differs from the plain launches"
+
+
+@pytest.mark.parametrize("tile,name", [(0, "256x256"), (1, "128x256"), (2, "192x128")])
+def test_every_gemm_tile_on_ragged_shapes(mq, tile, name, monkeypatch):
+    """The dispatcher picks a tile from a cost model; this forces each compiled tile in turn
+    (a tuning hook of the library) so that all of them see ragged T and N, one k-block and
+    many, whatever the model prefers."""
+    monkeypatch.setenv("MQUANT_TUNE_TILE", str(tile))
+    rng = np.random.default_rng(900 + tile)
+    for T, N, K in [(33, 40, 128), (200, 136, 384), (450, 520, 1024), (577, 300, 2048)]:
+        say(f"tile {name} T={T} N={N} K={K}")
+        xq = rng.integers(-128, 128, size=(T, K), dtype=np.int8)
+        packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+        w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+        V = T // 3
+        acc_want = orc.gemm_i8_i4_i32(xq, orc.unpack_w4(packed))
+        ref, _ = orc.dequant(acc_want, V, 0.07, 0.009, w_scale)
+        acc = torch.full((T, N), -7, dtype=torch.int32, device="cuda")
+        y = mq.w4a8_gemm(dev(xq), mq.w4_prepack(dev(packed)), dev(w_scale), N, V, 0.07, 0.009, acc_out=acc)
+        assert (acc.cpu().numpy() == acc_want).all(), (name, T, N, K)
+        check_y(y.cpu().numpy(), ref, f"tile {name} {(T, N, K)}")
+        y2 = mq.w4a8_gemm(dev(xq), mq.w4_prepack(dev(packed)), dev(w_scale), N, V, 0.07, 0.009)
+        check_y(y2.cpu().numpy(), ref, f"tile {name}, wide stores {(T, N, K)}")
