@@ -29,6 +29,14 @@
  *   - Matrices are row-major.  fp16 means IEEE binary16.  Leading dimensions
  *     are in elements.
  *   - Inputs must be finite; NaN/Inf behaviour is undefined.
+ *   - Entry points may be called from several host threads and on several
+ *     streams; calls that share an output buffer or a workspace must be
+ *     ordered by the caller.
+ *   - Environment (read at call time, for diagnosis and tuning only):
+ *     MQUANT_DEBUG=1 prints the HIP error text behind an ERR_HIP status;
+ *     MQUANT_TUNE_TILE=0|1|2 forces the GEMM tile (256x256, 128x256, 192x128)
+ *     instead of the cost model's choice; MQUANT_TUNE_NOSPLIT=1 disables
+ *     split-K.  Results do not depend on either choice.
  */
 #ifndef MQUANT_H
 #define MQUANT_H
