@@ -36,7 +36,8 @@
  *     MQUANT_DEBUG=1 prints the HIP error text behind an ERR_HIP status;
  *     MQUANT_TUNE_TILE=0|1|2 forces the GEMM tile (256x256, 128x256, 192x128)
  *     instead of the cost model's choice; MQUANT_TUNE_NOSPLIT=1 disables
- *     split-K.  Results do not depend on either choice.
+ *     split-K; MQUANT_TUNE_G128_TILE=0|1 forces the weight-only GEMM tile
+ *     (128x256, 96x256).  Results do not depend on these choices.
  */
 #ifndef MQUANT_H
 #define MQUANT_H

@@ -11,6 +11,7 @@
 namespace mquant {
 
 constexpr int kWave = 64;                 // CDNA wavefront width
+constexpr int kNumCU = 256;               // compute units of an MI355X
 
 static inline bool aligned_to(const void *p, uintptr_t a)
 {

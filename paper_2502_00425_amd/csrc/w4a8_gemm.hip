@@ -881,7 +881,6 @@ int check_gemm_args(const void *xq, const void *wp, const void *w_scale, const v
     return MQUANT_OK;
 }
 
-constexpr int kNumCU = 256;
 
 // Split-K plan for the 256x256 tile: when the tile grid fills less than half of
 // the CUs and K is long, S work-groups share a tile's K range, write int32

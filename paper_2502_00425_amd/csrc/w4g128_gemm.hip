@@ -515,8 +515,7 @@ extern "C" int mquant_w4g128_gemm(const void *x, int64_t ldx, const uint8_t *wp,
     hipStream_t st = static_cast<hipStream_t>(stream);
     // Decode shapes stream the weights through the GEMV.  In the GEMM every wave owns 32
     // output channels of the tile (WM = 1): a weight is dequantised once
-    // per work-group.  128 x 256 was the fastest tile on all four projection shapes of the
-    // 7B model at T = 1280.
+    // per work-group.
     const int32_t n_tiles32 = static_cast<int32_t>(ceil_div(N, kPackN));
     if (T <= 32 || (T <= 64 && n_tiles32 < 512)) {
         const int64_t w_bytes = static_cast<int64_t>(n_tiles32) * (K / kPackK) * kPackTileBytes;
@@ -545,5 +544,13 @@ extern "C" int mquant_w4g128_gemm(const void *x, int64_t ldx, const uint8_t *wp,
         return MQUANT_OK;
     }
     if (T <= 64) return launch_g128<64, 128, 1, 4>(xh, ldx, wp, yh, ldy, T, N, K, st);
+    // 96 x 256 when it fills more CUs per round than 128 x 256 (rounds over the CUs x tile
+    // rows / measured relative efficiency): 1280 x 3584 makes 196 tiles instead of 140 and
+    // runs 12 % faster; with thousands of tiles the taller tile wins by 15 %.
+    const double c128 = static_cast<double>(ceil_div(ceil_div(T, 128) * ceil_div(N, 256), kNumCU)) * 128.0;
+    const double c96 = static_cast<double>(ceil_div(ceil_div(T, 96) * ceil_div(N, 256), kNumCU)) * 96.0 / 0.9;
+    int tile = c96 < c128 ? 1 : 0;
+    if (const char *e = getenv("MQUANT_TUNE_G128_TILE")) { if (*e) tile = atoi(e); }
+    if (tile == 1) return launch_g128<96, 256, 1, 8>(xh, ldx, wp, yh, ldy, T, N, K, st);
     return launch_g128<128, 256, 1, 8>(xh, ldx, wp, yh, ldy, T, N, K, st);
 }
