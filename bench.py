@@ -35,7 +35,7 @@ FP16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense fp16, published
 # --pmc runs summarised in profiles/gemm_c1_prefill_hbm_traffic_pmc.md (FETCH_SIZE x 2.000,
 # WRITE_SIZE x 1.000, factors from a plain 1 GiB copy; includes the split-K partials of down).  A counter run cannot happen inside
 # this script; re-measure when the GEMM kernel or its tile order changes.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = 154.8e6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = 159.0e6
 
 
 def parse_args():
