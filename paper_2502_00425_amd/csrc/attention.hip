@@ -31,7 +31,7 @@ constexpr int kHeadDim = 128;          // the only head size built (28 x 128, 64
 constexpr int kBQ = 128;               // queries per work-group (32 per wave)
 constexpr int kBK = 64;                // keys per tile
 constexpr int kKPitch = 2 * kHeadDim + 16;   // bytes per key row in LDS: rows 4 banks apart
-constexpr int kVPitch = 2 * kBK + 8;         // bytes per V^T row (one head channel, 64 keys)
+constexpr int kVPitch = 2 * kBK + 16;        // bytes per V^T row (one head channel, 64 keys); 16-byte reads of 16 rows cover the 64 banks once
 
 // MFMA 32x32 result register r of lane group g holds row (r/4)*8 + g*4 + r%4.
 __device__ __forceinline__ int acc_row(int r, int g) { return (r >> 2) * 8 + g * 4 + (r & 3); }
@@ -209,10 +209,13 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
             const int c = tid + 256 * i, row = c >> 4, col = c & 15;
             *reinterpret_cast<v4u *>(k_lds2[b] + row * kKPitch + col * 16) = kreg[i];
         }
+        // The 4-key chunks of a row are stored so that the two chunks an MFMA operand needs
+        // (chunks 4 kk + g and 4 kk + 2 + g for lane group g) sit next to each other.
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int c = tid + 256 * i, d = c >> 4, col = c & 15;
-            *reinterpret_cast<v2u *>(v_lds2[b] + d * kVPitch + col * 8) = vreg[i];
+            const int slot = (col & 12) | ((col & 1) << 1) | ((col >> 1) & 1);
+            *reinterpret_cast<v2u *>(v_lds2[b] + d * kVPitch + slot * 8) = vreg[i];
         }
         if (tid < kBK) pos_lds2[b][tid] = preg;
     };
@@ -306,16 +309,10 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
             for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) {
-                    // operand slot i of lane group g is key kk*16 + (i/4)*8 + g*4 + i%4
-                    const uint8_t *vrow = v_lds + (dt * 32 + l32) * kVPitch + g * 8 + kk * 32;
-                    const v4h lo = *reinterpret_cast<const v4h *>(vrow);
-                    const v4h hi = *reinterpret_cast<const v4h *>(vrow + 16);
-                    v8h a;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        a[i] = lo[i];
-                        a[4 + i] = hi[i];
-                    }
+                    // operand slot i of lane group g is key kk*16 + (i/4)*8 + g*4 + i%4: one
+                    // 16-byte read in the chunk order the staging wrote
+                    const v8h a = *reinterpret_cast<const v8h *>(
+                        v_lds + (dt * 32 + l32) * kVPitch + kk * 32 + g * 16);
                     acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p[kk], acc_o[dt], 0, 0, 0);
                 }
         }
