@@ -6,7 +6,9 @@
 // is 1024): lane l holds channels 8l..8l+7, so index bits 0-2 live in a lane's
 // registers and bits 3-8 across the 64 lanes.  The butterflies run in the fixed
 // stage order h = 1, 2, 4, ..., B/2, one fp32 add or subtract each, which is
-// what makes the int8 codes reproducible bit for bit.
+// what makes the int8 codes reproducible bit for bit.  After load_rotate the registers
+// of some lanes hold the exact negative of the rotated value (lane_sign_bit); absmax
+// does not care and quant_store folds the sign into its multiplier.
 #pragma once
 
 #include <hip/hip_fp16.h>
@@ -61,20 +63,58 @@ __device__ __forceinline__ float lane_xor(float x, int lane)
     return __int_as_float(r);
 }
 
+// Lanes whose values carry a minus sign after the in-row stages (see lane_stage): the
+// parity of the lane-index bits those stages paired on.
+template <int B>
+__device__ __forceinline__ uint32_t lane_sign_bit(int lane)
+{
+    constexpr int bits = B >= 128 ? 15 : (B >= 64 ? 7 : (B >= 32 ? 3 : (B >= 16 ? 1 : 0)));
+    return (__builtin_popcount(lane & bits) & 1) ? 0x80000000u : 0u;
+}
+
+// v += c * (v of lane ^ M) in one instruction: the DPP operand of v_fmac_f32 fetches
+// the partner lane's value.  c is +-1, so the product is exact and the result is the
+// correctly rounded sum or difference, as a separate add would give.
+template <int M>
+__device__ __forceinline__ void fmac_lane_xor(float &v, float c)
+{
+    static_assert(M == 1 || M == 2 || M == 4 || M == 8, "in-row distance");
+    if constexpr (M == 1) {
+        asm volatile("v_fmac_f32_dpp %0, %0, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf"
+                     : "+v"(v) : "v"(c));
+    } else if constexpr (M == 2) {
+        asm volatile("v_fmac_f32_dpp %0, %0, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
+                     : "+v"(v) : "v"(c));
+    } else if constexpr (M == 8) {
+        asm volatile("v_fmac_f32_dpp %0, %0, %1 row_ror:8 row_mask:0xf bank_mask:0xf"
+                     : "+v"(v) : "v"(c));
+    } else {
+        // i -> 7 - i inside each group of 8, then the quad reversed: i -> i ^ 4
+        float t;
+        asm volatile("v_mov_b32_dpp %0, %1 row_half_mirror row_mask:0xf bank_mask:0xf"
+                     : "=v"(t) : "v"(v));
+        asm volatile("v_fmac_f32_dpp %0, %1, %2 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf"
+                     : "+v"(v) : "v"(t), "v"(c));
+    }
+}
+
 template <int B, int M>
 __device__ __forceinline__ void lane_stage(float (&v)[8], int lane)
 {
     if constexpr (8 * M < B) {
         if constexpr (M < 16) {
-            // The lane holding the lower index keeps a + b, the other one a - b with
-            // a the lower-index value: other + (upper ? -mine : mine), one add each.
-            const int sign = (lane & M) ? static_cast<int>(0x80000000u) : 0;
+            // Butterfly between lane l (lower index, bit M clear) and l ^ M: the lower lane
+            // must end with a + b, the upper one with a - b, a being the lower lane's value.
+            // Each lane computes mine + c * other with c = +1 (lower) or -1 (upper): the
+            // lower lane gets a + b, the upper lane b - a = -(a - b).  The minus sign is
+            // not repaired here: a value that is the exact negative of the true one stays
+            // the exact negative through every later add and subtract (IEEE rounding is
+            // symmetric), both partners of a later stage carry the same sign, and the
+            // quantizer multiplies by a constant whose sign is flipped for those lanes
+            // (lane_sign_bit).  One instruction per element and stage.
+            const float c = (lane & M) ? -1.0f : 1.0f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float other = lane_xor<M>(v[j], lane);
-                const float mine = __int_as_float(__float_as_int(v[j]) ^ sign);
-                v[j] = other + mine;
-            }
+            for (int j = 0; j < 8; ++j) fmac_lane_xor<M>(v[j], c);
         } else {
             // Partner lanes sit in different rows (M = 16) or wave halves (M = 32).
             // The row / half swap instructions exchange the odd rows (upper half)
@@ -197,9 +237,11 @@ struct Segment {
                 // rounds to an integer (ties to even) and leaves it in the low mantissa
                 // bits, whose low byte is the two's-complement int8 code.
                 uint32_t bits[8];
+                // lanes that hold the exact negative of the rotated value multiply by -cmul
+                const float cm = __uint_as_float(__float_as_uint(cmul) ^ lane_sign_bit<B>(lane));
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const float t = __builtin_amdgcn_fmed3f(v[c][j] * cmul, q_lo, q_hi);
+                    const float t = __builtin_amdgcn_fmed3f(v[c][j] * cm, q_lo, q_hi);
                     bits[j] = __float_as_uint(t + 12582912.0f);
                 }
                 uint32_t packed[2];
