@@ -72,31 +72,70 @@ __device__ __forceinline__ uint32_t lane_sign_bit(int lane)
     return (__builtin_popcount(lane & bits) & 1) ? 0x80000000u : 0u;
 }
 
-// v += c * (v of lane ^ M) in one instruction: the DPP operand of v_fmac_f32 fetches
-// the partner lane's value.  c is +-1, so the product is exact and the result is the
-// correctly rounded sum or difference, as a separate add would give.
+// v[j] += c * (v[j] of lane ^ M) for the eight registers of a lane, one instruction per
+// register: the DPP operand of v_fmac_f32 fetches the partner lane's value.  c is +-1, so
+// the product is exact and the result is the correctly rounded sum or difference, as a
+// separate add would give.  A DPP operand must not be read within two wait states of the
+// VALU write that produced it, and the compiler does not see into the statement: the
+// leading s_nop covers whatever wrote the registers last, and inside the block a register
+// is read at least eight instructions after it was written.
+#define MQ_FMAC8(CTRL)                                                                         \
+    asm volatile("s_nop 1\n\t"                                                                 \
+                 "v_fmac_f32_dpp %0, %0, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"            \
+                 "v_fmac_f32_dpp %1, %1, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"            \
+                 "v_fmac_f32_dpp %2, %2, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"            \
+                 "v_fmac_f32_dpp %3, %3, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"            \
+                 "v_fmac_f32_dpp %4, %4, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"            \
+                 "v_fmac_f32_dpp %5, %5, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"            \
+                 "v_fmac_f32_dpp %6, %6, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"            \
+                 "v_fmac_f32_dpp %7, %7, %8 " CTRL " row_mask:0xf bank_mask:0xf"                \
+                 : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]),     \
+                   "+v"(v[6]), "+v"(v[7])                                                      \
+                 : "v"(c))
+
 template <int M>
-__device__ __forceinline__ void fmac_lane_xor(float &v, float c)
+__device__ __forceinline__ void fmac_lane_xor(float (&v)[8], float c)
 {
     static_assert(M == 1 || M == 2 || M == 4 || M == 8, "in-row distance");
     if constexpr (M == 1) {
-        asm volatile("v_fmac_f32_dpp %0, %0, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf"
-                     : "+v"(v) : "v"(c));
+        MQ_FMAC8("quad_perm:[1,0,3,2]");
     } else if constexpr (M == 2) {
-        asm volatile("v_fmac_f32_dpp %0, %0, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
-                     : "+v"(v) : "v"(c));
+        MQ_FMAC8("quad_perm:[2,3,0,1]");
     } else if constexpr (M == 8) {
-        asm volatile("v_fmac_f32_dpp %0, %0, %1 row_ror:8 row_mask:0xf bank_mask:0xf"
-                     : "+v"(v) : "v"(c));
+        MQ_FMAC8("row_ror:8");
     } else {
-        // i -> 7 - i inside each group of 8, then the quad reversed: i -> i ^ 4
-        float t;
-        asm volatile("v_mov_b32_dpp %0, %1 row_half_mirror row_mask:0xf bank_mask:0xf"
-                     : "=v"(t) : "v"(v));
-        asm volatile("v_fmac_f32_dpp %0, %1, %2 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf"
-                     : "+v"(v) : "v"(t), "v"(c));
+        // i -> 7 - i inside each group of 8 into temporaries, then the quad reversed as the
+        // DPP operand of the multiply-add: i -> i ^ 4
+        float t[8];
+        asm volatile("s_nop 1\n\t"
+                     "v_mov_b32_dpp %0, %8 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                     "v_mov_b32_dpp %1, %9 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                     "v_mov_b32_dpp %2, %10 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                     "v_mov_b32_dpp %3, %11 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                     "v_mov_b32_dpp %4, %12 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                     "v_mov_b32_dpp %5, %13 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                     "v_mov_b32_dpp %6, %14 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                     "v_mov_b32_dpp %7, %15 row_half_mirror row_mask:0xf bank_mask:0xf"
+                     : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]),
+                       "=&v"(t[6]), "=&v"(t[7])
+                     : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]),
+                       "v"(v[7]));
+        asm volatile("s_nop 1\n\t"
+                     "v_fmac_f32_dpp %0, %8, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+                     "v_fmac_f32_dpp %1, %9, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+                     "v_fmac_f32_dpp %2, %10, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+                     "v_fmac_f32_dpp %3, %11, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+                     "v_fmac_f32_dpp %4, %12, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+                     "v_fmac_f32_dpp %5, %13, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+                     "v_fmac_f32_dpp %6, %14, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+                     "v_fmac_f32_dpp %7, %15, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf"
+                     : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]),
+                       "+v"(v[6]), "+v"(v[7])
+                     : "v"(t[0]), "v"(t[1]), "v"(t[2]), "v"(t[3]), "v"(t[4]), "v"(t[5]), "v"(t[6]),
+                       "v"(t[7]), "v"(c));
     }
 }
+#undef MQ_FMAC8
 
 template <int B, int M>
 __device__ __forceinline__ void lane_stage(float (&v)[8], int lane)
@@ -113,8 +152,7 @@ __device__ __forceinline__ void lane_stage(float (&v)[8], int lane)
             // quantizer multiplies by a constant whose sign is flipped for those lanes
             // (lane_sign_bit).  One instruction per element and stage.
             const float c = (lane & M) ? -1.0f : 1.0f;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) fmac_lane_xor<M>(v[j], c);
+            fmac_lane_xor<M>(v, c);
         } else {
             // Partner lanes sit in different rows (M = 16) or wave halves (M = 32).
             // The row / half swap instructions exchange the odd rows (upper half)
