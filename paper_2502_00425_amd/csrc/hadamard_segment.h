@@ -34,35 +34,6 @@ __device__ __forceinline__ void register_stages(float (&v)[8])
     }
 }
 
-// Value of lane (l ^ M) for M in {1, 2, 4, 8, 16, 32}, without touching LDS
-// memory: DPP quad/row permutes inside a row of 16 lanes, a swizzle across the
-// two rows of a half-wave, the half-wave swap instruction across the halves.
-template <int M>
-__device__ __forceinline__ float lane_xor(float x, int lane)
-{
-    const int xi = __float_as_int(x);
-    int r;
-    if constexpr (M == 1) {
-        r = __builtin_amdgcn_update_dpp(0, xi, 0xB1, 0xF, 0xF, true);       // quad_perm [1,0,3,2]
-    } else if constexpr (M == 2) {
-        r = __builtin_amdgcn_update_dpp(0, xi, 0x4E, 0xF, 0xF, true);       // quad_perm [2,3,0,1]
-    } else if constexpr (M == 4) {
-        // i -> 7 - i inside each group of 8, then reverse inside each quad: i -> i ^ 4
-        const int t = __builtin_amdgcn_update_dpp(0, xi, 0x141, 0xF, 0xF, true);   // row_half_mirror
-        r = __builtin_amdgcn_update_dpp(0, t, 0x1B, 0xF, 0xF, true);               // quad_perm [3,2,1,0]
-    } else if constexpr (M == 8) {
-        r = __builtin_amdgcn_update_dpp(0, xi, 0x128, 0xF, 0xF, true);      // row_ror:8
-    } else if constexpr (M == 16) {
-        r = __builtin_amdgcn_ds_swizzle(xi, 0x401F);                        // bit mode, xor 16
-    } else {
-        static_assert(M == 32, "lane_xor distance");
-        // {x[0..31], x[0..31]} and {x[32..63], x[32..63]}
-        const auto sw = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
-        r = lane < 32 ? sw[1] : sw[0];
-    }
-    return __int_as_float(r);
-}
-
 // Lanes whose values carry a minus sign after the in-row stages (see lane_stage): the
 // parity of the lane-index bits those stages paired on.
 template <int B>
