@@ -77,6 +77,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
+    from paper_2502_00425_amd import build as hip_build
+    if not os.path.exists(hip_build.LIB):                # load what is built; build only if nothing is
+        hip_build.build(force=True)
     import paper_2502_00425_amd as pkg
     from paper_2502_00425_amd import binding as mq       # raises if libmquant.so is missing
     from paper_2502_00425_amd import workloads as wl
