@@ -302,6 +302,36 @@ def test_gemm_extreme_values_no_overflow(mq):
     assert (acc1.cpu().numpy() == acc_want[:2]).all()
 
 
+def test_gemm_at_the_maximum_k(mq):
+    """K = 65536 is the documented limit: the accumulator holds 16 x the sum, and with every
+    activation at -128 and every weight at -8 that is 2^30, the largest value it can take.
+    Closed form (every product equal) for the accumulators, the oracle for the mixed rows;
+    the GEMV, the direct GEMM, split-K with its workspace, and the wide and the 2-byte stores."""
+    K, N = 65536, 72
+    say(f"gemm at K={K}")
+    packed = np.full((N, K // 2), 0x88, dtype=np.uint8)          # every weight -8
+    packed[1::2] = 0x77                                          # every weight +7
+    wq = orc.unpack_w4(packed)
+    wp = mq.w4_prepack(dev(packed))
+    ones = dev(np.ones(N, dtype=np.float16))
+    for T in (3, 40, 300):
+        xq = np.full((T, K), -128, dtype=np.int8)
+        xq[1::3] = 127
+        xq[2::3, ::2] = 55                                       # a row with mixed values
+        acc_want = orc.gemm_i8_i4_i32(xq, wq)
+        assert acc_want[0, 0] == K * 1024 == 2 ** 26 and acc_want[0, 1] == -K * 128 * 7
+        nws = mq.w4a8_workspace_bytes(T, N, K)
+        ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+        acc = torch.empty((T, N), dtype=torch.int32, device="cuda")
+        y = mq.w4a8_gemm(dev(xq), wp, ones, N, 0, 2.0 ** -20, 2.0 ** -20, acc_out=acc, workspace=ws)
+        assert (acc.cpu().numpy() == acc_want).all(), T
+        ref, _ = orc.dequant(acc_want, 0, 2.0 ** -20, 2.0 ** -20, np.ones(N, dtype=np.float16))
+        check_y(y.cpu().numpy(), ref, f"max K, T={T}")
+        y2 = mq.w4a8_gemm(dev(xq), wp, ones, N, 0, 2.0 ** -20, 2.0 ** -20, workspace=ws)
+        check_y(y2.cpu().numpy(), ref, f"max K, no acc_out, T={T}")
+    assert mq.lib.mquant_w4_prepacked_bytes(N, K + 64) == mq.ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("T", [1, 2, 4, 16, 31, 32])
 def test_gemv_small_shapes_full(mq, T):
     say(f"gemv T={T}")
