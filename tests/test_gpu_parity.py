@@ -592,3 +592,75 @@ def test_every_gemm_tile_on_ragged_shapes(mq, tile, name, monkeypatch):
         check_y(y.cpu().numpy(), ref, f"tile {name} {(T, N, K)}")
         y2 = mq.w4a8_gemm(dev(xq), mq.w4_prepack(dev(packed)), dev(w_scale), N, V, 0.07, 0.009)
         check_y(y2.cpu().numpy(), ref, f"tile {name}, wide stores {(T, N, K)}")
+
+
+def test_gemm_output_beyond_2_31_elements(mq):
+    """T x N > 2^31 outputs (5.3 GB of fp16): every index that addresses y must be 64-bit.
+    Rows from both ends and from either side of the 2^31-element mark are compared with the
+    oracle; K is one k-block so that the run is short."""
+    T, N, K = 70000, 37888, 128
+    assert T * N > 2 ** 31
+    say(f"gemm T={T} N={N} K={K} (y has {T * N / 2 ** 31:.2f} x 2^31 elements)")
+    rng = np.random.default_rng(231)
+    V = 40000
+    xq = torch.randint(-128, 128, (T, K), dtype=torch.int8, device="cuda",
+                       generator=torch.Generator(device="cuda").manual_seed(5))
+    packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+    y = torch.full((T, N), 9.0, dtype=torch.float16, device="cuda")
+    mq.w4a8_gemm(xq, mq.w4_prepack(dev(packed)), dev(w_scale), N, V, 0.07, 0.009, out=y)
+    torch.cuda.synchronize()
+    mark = 2 ** 31 // N                                          # the row that holds element 2^31
+    rows = np.array([0, 1, 255, 256, V - 1, V, mark - 1, mark, mark + 1, T - 257, T - 2, T - 1])
+    got = y[torch.from_numpy(rows).cuda()].cpu().numpy()
+    acc_want = orc.gemm_i8_i4_i32(xq[torch.from_numpy(rows).cuda()].cpu().numpy(), orc.unpack_w4(packed))
+    for i, r in enumerate(rows):
+        ref, _ = orc.dequant(acc_want[i:i + 1], 1 if r < V else 0, 0.07, 0.009, w_scale)
+        check_y(got[i:i + 1], ref, f"row {r}")
+    # every row was written (9.0 survives nowhere): a device-side reduction over all 2.65e9 outputs
+    assert not bool((y == 9.0).all(dim=1).any().item())
+    del y
+    torch.cuda.empty_cache()
+
+
+def test_front_end_and_mask_beyond_2_31_elements(mq):
+    """The same 64-bit index check for the row permute, the rotate+quant front end (T x K >
+    2^31) and the mask remap (T^2 > 2^31), on sampled rows."""
+    T, K, B = 70000, 32768, 512
+    assert T * K > 2 ** 31
+    say(f"front end T={T} K={K}")
+    g = torch.Generator(device="cuda").manual_seed(9)
+    x = torch.empty((T, K), dtype=torch.float16, device="cuda")
+    for r0 in range(0, T, 10000):                            # filled in slabs: no fp32 temporary of 9 GB
+        x[r0:r0 + 10000] = torch.randn((min(10000, T - r0), K), device="cuda", generator=g).half()
+    spans = [(5, 30000), (40000, 20000)]
+    perm, _, V = mq.aifs_build_perm(T, spans)
+    permd = dev(perm)
+    rows = np.array([0, 1, V - 1, V, 2 ** 31 // K - 1, 2 ** 31 // K, 2 ** 31 // K + 1, T - 2, T - 1])
+    rd = torch.from_numpy(rows).cuda()
+    src = x[torch.from_numpy(perm[rows].astype(np.int64)).cuda()].cpu().numpy()     # rows of E^u
+    xq = mq.hadamard_quant_act(x, V, 0.11, 0.07, B, perm_dev=permd)
+    got = xq[rd].cpu().numpy()
+    for i, r in enumerate(rows):
+        want = orc.msq_quantize(orc.hadamard_rotate(src[i:i + 1], B), 1 if r < V else 0, 0.11, 0.07, B)
+        assert (got[i:i + 1] == want).all(), f"codes of row {r}"
+    del xq
+    xu = mq.aifs_permute(x, permd)
+    assert (xu[rd].cpu().numpy().view(np.uint16) == src.view(np.uint16)).all()
+    del xu, x
+    torch.cuda.empty_cache()
+
+    Tm = 47000
+    assert Tm * Tm > 2 ** 31
+    say(f"mask remap T={Tm}")
+    perm2, _, _ = mq.aifs_build_perm(Tm, [(100, 20000), (30000, 9000)])
+    mask = torch.tril(torch.ones((Tm, Tm), dtype=torch.uint8, device="cuda"))
+    mu = mq.aifs_remap_mask(mask, dev(perm2))
+    del mask
+    rows2 = np.array([0, 1, 19999, 20000, 2 ** 31 // Tm, 2 ** 31 // Tm + 1, Tm - 1])
+    got2 = mu[torch.from_numpy(rows2).cuda()].cpu().numpy()
+    for i, r in enumerate(rows2):
+        want = (perm2 <= perm2[r]).astype(np.uint8)          # M^u[i, j] = M[perm[i], perm[j]], M causal
+        assert (got2[i] == want).all(), f"mask row {r}"
+    del mu
+    torch.cuda.empty_cache()
