@@ -160,3 +160,24 @@ def test_both_gemm_tiles_on_ragged_shapes(mq, tile, monkeypatch):
         say(f"tile {tile} T={T} N={N} K={K}")
         y = mq.w4g128_gemm(dev(x), wp, N).cpu().numpy()
         check(y, ref, mag, f"w4g128 tile {tile} {(T, N, K)}")
+
+
+def test_output_beyond_2_31_elements(mq):
+    """T x N > 2^31 outputs: 64-bit addressing of y, on sampled rows (K = one group)."""
+    T, N, K = 70000, 37888, 128
+    rng = np.random.default_rng(77)
+    say(f"w4g128 T={T} N={N} K={K}")
+    wq = rng.integers(-8, 8, size=(N, K), dtype=np.int8)
+    sc = rng.uniform(0.002, 0.01, size=(N, 1)).astype(np.float16)
+    x = torch.randn((T, K), device="cuda", generator=torch.Generator(device="cuda").manual_seed(3)).half()
+    wp = mq.w4g128_prepack(dev(pack_int4(wq)), dev(sc))
+    y = torch.full((T, N), 9.0, dtype=torch.float16, device="cuda")
+    mq.w4g128_gemm(x, wp, N, out=y)
+    torch.cuda.synchronize()
+    mark = 2 ** 31 // N
+    rows = torch.tensor([0, 127, 128, mark - 1, mark, mark + 1, T - 129, T - 1], device="cuda")
+    ref, mag = orc.w4g128_linear(x[rows].cpu().numpy(), wq, sc)
+    check(y[rows].cpu().numpy(), ref, mag, "w4g128 beyond 2^31")
+    assert not bool((y == 9.0).all(dim=1).any().item())
+    del y
+    torch.cuda.empty_cache()
