@@ -673,6 +673,34 @@ def bench_decode(args, torch, mq, wl):
             res[name] = {"us_per_layer": round(ms_layer * 1e3, 2), "GBps": round(gbps, 1),
                          "frac": round(gbps / HBM_PEAK_GBPS, 4)}
         res["bytes_per_layer"] = bytes_layer
+        if T == 1:
+            # per projection: the same projection of every layer back to back (distinct weights,
+            # so nothing is served from the last-level cache), one HIP graph per projection
+            per_proj = {}
+            for proj, (K, N) in wd.projections.items():
+                def proj_pass(proj=proj, K=K, N=N):
+                    for layer in layers:
+                        _, _, wp, ws = layer[proj]
+                        mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
+                proj_pass()
+                torch.cuda.synchronize()
+                run = proj_pass
+                if not args.no_graphs:
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph):
+                        proj_pass()
+                    run = graph.replay
+                    run()
+                    torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.decode_iters):
+                    run()
+                torch.cuda.synchronize()
+                us = (time.perf_counter() - t0) * 1e6 / args.decode_iters / len(layers)
+                nbytes = K * N / 2 + 2 * N + T * K + 2 * T * N
+                per_proj[proj] = {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                                  "frac": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
+            res["per_projection_gemv"] = per_proj
         out["per_T"][f"T{T}"] = res
     del layers, fused_layers
     out["large_shapes_T1"] = bench_decode_large(args, torch, mq, wl, gen)
