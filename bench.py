@@ -78,10 +78,9 @@ def main():
     torch.cuda.set_device(0)
 
     from paper_2502_00425_amd import build as hip_build
-    if not os.path.exists(hip_build.LIB):                # load what is built; build only if nothing is
-        hip_build.build(force=True)
-    import paper_2502_00425_amd as pkg
+    hip_build.ensure_fresh()                             # load what is built unless its sources changed
     from paper_2502_00425_amd import binding as mq       # raises if libmquant.so is missing
+    from paper_2502_00425_amd import probes
     from paper_2502_00425_amd import workloads as wl
 
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -111,8 +110,8 @@ def main():
         lin[proj] = {
             "K": K, "N": N, "x": dev(inp["x"]),
             "wp": mq.w4_prepack(dev(inp["w_packed"])), "w_scale": dev(inp["w_scale"]),
-            "s_vis": pkg.static_scale_from_absmax(a[0], B),
-            "s_txt": pkg.static_scale_from_absmax(a[1], B),
+            "s_vis": mq.static_scale_from_absmax(a[0], B),
+            "s_txt": mq.static_scale_from_absmax(a[1], B),
             "xq": torch.empty((T, K), dtype=torch.int8, device="cuda"),
             "y": torch.empty((T, N), dtype=torch.float16, device="cuda"),
             "host": inp,
@@ -272,12 +271,12 @@ def main():
         zer = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
         sink = torch.zeros(4, dtype=torch.int32, device="cuda")
         iters = 20000
-        ops = float(mq.probe_mfma_i8(iters, rnd, sink))
-        att = {"mfma_i8_random_operands_TOPS": round(ops / timed_once(lambda: mq.probe_mfma_i8(iters, rnd, sink)) / 1e9, 1),
-               "mfma_i8_zero_operands_TOPS": round(ops / timed_once(lambda: mq.probe_mfma_i8(iters, zer, sink)) / 1e9, 1)}
+        ops = float(probes.mfma_i8(iters, rnd, sink))
+        att = {"mfma_i8_random_operands_TOPS": round(ops / timed_once(lambda: probes.mfma_i8(iters, rnd, sink)) / 1e9, 1),
+               "mfma_i8_zero_operands_TOPS": round(ops / timed_once(lambda: probes.mfma_i8(iters, zer, sink)) / 1e9, 1)}
         big = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
-        nbytes = float(mq.probe_hbm_read(big, sink))
-        att["hbm_read_GBps"] = round(nbytes / timed_once(lambda: mq.probe_hbm_read(big, sink)) / 1e6, 1)
+        nbytes = float(probes.hbm_read(big, sink))
+        att["hbm_read_GBps"] = round(nbytes / timed_once(lambda: probes.hbm_read(big, sink)) / 1e6, 1)
         del big
         torch.cuda.empty_cache()
         result["attainable"] = att

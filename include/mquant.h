@@ -32,12 +32,9 @@
  *   - Entry points may be called from several host threads and on several
  *     streams; calls that share an output buffer or a workspace must be
  *     ordered by the caller.
- *   - Environment (read at call time, for diagnosis and tuning only):
- *     MQUANT_DEBUG=1 prints the HIP error text behind an ERR_HIP status;
- *     MQUANT_TUNE_TILE=0|1|2 forces the GEMM tile (256x256, 128x256, 192x128)
- *     instead of the cost model's choice; MQUANT_TUNE_NOSPLIT=1 disables
- *     split-K; MQUANT_TUNE_G128_TILE=0|1 forces the weight-only GEMM tile
- *     (128x256, 96x256).  Results do not depend on these choices.
+ *   - Environment: MQUANT_DEBUG=1 prints the HIP error text behind an ERR_HIP
+ *     status.  Kernel choices (tile shapes, split-K) are made by the library's
+ *     cost model; mquant_tune_set() overrides them for tests and tuning runs.
  */
 #ifndef MQUANT_H
 #define MQUANT_H
@@ -70,6 +67,10 @@ typedef void *mquant_stream_t; /* hipStream_t */
 /* Library version (major*10000 + minor*100 + patch). */
 int mquant_version(void);
 
+/* Static, NUL-terminated hash of the sources and flags this binary was built from
+ * (what the build script computes; "unknown" for a build made without it). */
+const char *mquant_build_id(void);
+
 /* Static, NUL-terminated description of a status code. */
 const char *mquant_status_string(int status);
 
@@ -99,6 +100,8 @@ int mquant_aifs_build_perm(int32_t T, const mquant_span_t *vis_host, int32_t n_s
  * the reorder that replaces slice/concat of interleaved tokens).
  *   x_dev   : fp16 [T, K], leading dimension ldx  (read)
  *   x_u_dev : fp16 [T, K], leading dimension ldxu (written); must not alias x
+ *             (x_u_dev == x_dev is rejected with ERR_BAD_SHAPE; partial overlap is
+ *             the caller's responsibility)
  *   perm_dev: int32 [T], every entry in [0, T) (not checked on the device
  *             beyond a clamp: an out-of-range entry reads row 0)
  * Requirements: K % 8 == 0, ldx % 8 == 0, ldxu % 8 == 0, 16-byte aligned
@@ -163,11 +166,25 @@ int mquant_hadamard_quant_act_bits(const void *x_dev, int64_t ldx, const int32_t
  * calibration samples; Eq. (2): s = max|x| / 127): the maximum |u| over the
  * unnormalised rotation of all T rows, combined into *absmax_dev with max().
  * The caller zeroes *absmax_dev (a float in device memory) beforehand and
- * derives s = absmax / sqrt(B) / 127.  Same requirements as
- * mquant_hadamard_quant_act.
+ * turns the statistic into a scale with mquant_static_scale_from_absmax.  Same
+ * requirements as mquant_hadamard_quant_act.
  */
 int mquant_hadamard_absmax(const void *x_dev, int64_t ldx, int32_t T, int32_t K,
                            int32_t had_block, float *absmax_dev, mquant_stream_t stream);
+
+/*
+ * HOST, synchronous.  The static scale of Eq. (2), s = max|x_rot| / (2^(b-1) - 1),
+ * from the statistic mquant_hadamard_absmax returns: x_rot = u / sqrt(had_block)
+ * is the orthonormal rotation, so
+ *     *scale_host = fp32( absmax_u / sqrt(had_block) / (2^(act_bits-1) - 1) ),
+ * evaluated in double and rounded once.  act_bits = 8 for the W4A8 path.
+ * Errors: ERR_NULL (scale_host), ERR_UNSUPPORTED (had_block not a power of two in
+ * [1, 1024], act_bits outside 2..8), ERR_BAD_SHAPE (absmax_u negative or not finite).
+ * absmax_u == 0 (an all-zero calibration set) yields scale 0, which the quantizer
+ * entry points reject: the caller decides what an empty statistic means.
+ */
+int mquant_static_scale_from_absmax(float absmax_u, int32_t had_block, int32_t act_bits,
+                                    float *scale_host);
 
 /*
  * DEVICE.  Per-token dynamic activation quantization, the baseline the speed
@@ -398,27 +415,23 @@ int mquant_w4g128_gemm(const void *x_dev, int64_t ldx, const uint8_t *w_prepacke
                        int64_t ldy, int32_t T, int32_t N, int32_t K, mquant_stream_t stream);
 
 /* -------------------------------------------------------------------------
- * Measurement probes.  Not part of the method: they measure what this chip
- * attains on the two resources the path is bound by (for the benchmark's
- * "attainable" figures).  Both are DEVICE calls, asynchronous like the rest.
+ * Tuning hook (tests and tuning runs; not needed for normal use).
  * ---------------------------------------------------------------------- */
 
-/* int8 operations one mquant_probe_mfma_i8(iters) launch performs. */
-int64_t mquant_probe_mfma_i8_ops(int32_t iters);
+typedef enum {
+    MQUANT_TUNE_GEMM_TILE = 0,      /* -1 = cost model; 0 = 256x256, 1 = 128x256, 2 = 192x128 */
+    MQUANT_TUNE_GEMM_NOSPLIT = 1,   /* 0 = cost model; 1 = never split K */
+    MQUANT_TUNE_G128_TILE = 2       /* -1 = cost model; 0 = 128x256, 1 = 96x256 (weight-only GEMM) */
+} mquant_tune_key_t;
 
 /*
- * An MFMA-only loop (v_mfma_i32_32x32x32_i8, eight independent accumulators
- * per wave, four waves per SIMD on every CU) whose operands are read once from
- * data_dev (>= 4096 bytes, 16-byte aligned; its contents set the data-dependent
- * matrix clock: zeros, or random bytes as in a real product).  sink_dev: one
- * int32 that is practically never written.
+ * HOST.  Overrides one kernel choice of the library for the whole process until
+ * it is set back (value -1, or 0 for NOSPLIT).  Results never depend on these
+ * choices, only speed; workspace sizes reported before a change may no longer
+ * match (NOSPLIT needs none).  Out-of-range keys or values: ERR_BAD_SHAPE and
+ * nothing changes.  Thread-safe; calls already running keep the value they read.
  */
-int mquant_probe_mfma_i8(int32_t iters, const void *data_dev, int64_t data_bytes, int32_t *sink_dev,
-                         mquant_stream_t stream);
-
-/* A read-only stream over data_bytes of data_dev (16-byte aligned), 16 bytes per lane. */
-int mquant_probe_hbm_read(const void *data_dev, int64_t data_bytes, uint32_t *sink_dev,
-                          mquant_stream_t stream);
+int mquant_tune_set(int32_t key, int32_t value);
 
 #ifdef __cplusplus
 }

@@ -29,8 +29,8 @@ EXPORTS = (
     "mquant_w4a8_gemm", "mquant_w4a8_linear_prefill_workspace_bytes", "mquant_w4a8_linear_prefill",
     "mquant_hadamard_dynquant_act", "mquant_w4a8_gemm_rowscale", "mquant_w4a8_gemm_rms",
     "mquant_rope_apply", "mquant_aifs_attention_workspace_bytes", "mquant_aifs_attention",
-    "mquant_hadamard_quant_act_bits",
-    "mquant_probe_mfma_i8_ops", "mquant_probe_mfma_i8", "mquant_probe_hbm_read",
+    "mquant_hadamard_quant_act_bits", "mquant_static_scale_from_absmax", "mquant_tune_set",
+    "mquant_build_id",
     "mquant_w4a8_linear_decode",
     "mquant_w4g128_prepacked_bytes", "mquant_w4g128_prepack", "mquant_w4g128_gemm",
 )
@@ -58,6 +58,10 @@ def _load() -> ctypes.CDLL:
     lib.mquant_version.restype = ctypes.c_int
     lib.mquant_status_string.restype = ctypes.c_char_p
     lib.mquant_status_string.argtypes = [ctypes.c_int]
+    lib.mquant_build_id.restype = ctypes.c_char_p
+    lib.mquant_build_id.argtypes = []
+    lib.mquant_static_scale_from_absmax.argtypes = [f32, i32, i32, p]
+    lib.mquant_tune_set.argtypes = [i32, i32]
     lib.mquant_aifs_build_perm.argtypes = [i32, p, i32, p, p, p]
     lib.mquant_aifs_permute.argtypes = [p, i64, p, i64, p, i32, i32, p]
     lib.mquant_aifs_remap_mask.argtypes = [p, p, p, i32, p]
@@ -87,13 +91,9 @@ def _load() -> ctypes.CDLL:
     lib.mquant_w4g128_prepacked_bytes.argtypes = [i32, i32]
     lib.mquant_w4g128_prepack.argtypes = [p, p, p, i32, i32, p]
     lib.mquant_w4g128_gemm.argtypes = [p, i64, p, p, i64, i32, i32, i32, p]
-    lib.mquant_probe_mfma_i8_ops.restype = i64
-    lib.mquant_probe_mfma_i8_ops.argtypes = [i32]
-    lib.mquant_probe_mfma_i8.argtypes = [i32, p, i64, p, p]
-    lib.mquant_probe_hbm_read.argtypes = [p, i64, p, p]
     for name in EXPORTS:
         if name not in ("mquant_status_string", "mquant_w4_prepacked_bytes", "mquant_aifs_attention_workspace_bytes",
-                        "mquant_probe_mfma_i8_ops", "mquant_w4g128_prepacked_bytes",
+                        "mquant_build_id", "mquant_w4g128_prepacked_bytes",
                         "mquant_w4a8_workspace_bytes", "mquant_w4a8_linear_prefill_workspace_bytes",
                         "mquant_version"):
             getattr(lib, name).restype = ctypes.c_int
@@ -111,6 +111,26 @@ def version() -> int:
     return int(lib.mquant_version())
 
 
+def build_id() -> str:
+    return lib.mquant_build_id().decode()
+
+
+TUNE_GEMM_TILE, TUNE_GEMM_NOSPLIT, TUNE_G128_TILE = 0, 1, 2
+
+
+def tune_set(key: int, value: int) -> None:
+    _check(lib.mquant_tune_set(int(key), int(value)), "mquant_tune_set")
+
+
+def static_scale_from_absmax(absmax_u: float, had_block: int, act_bits: int = 8) -> float:
+    """Eq. (2)'s static scale from the statistic of ``hadamard_absmax`` (computed by the library)."""
+    out = ctypes.c_float(0.0)
+    _check(lib.mquant_static_scale_from_absmax(float(absmax_u), int(had_block), int(act_bits),
+                                               ctypes.cast(ctypes.byref(out), ctypes.c_void_p)),
+           "mquant_static_scale_from_absmax")
+    return float(out.value)
+
+
 def _check(status: int, where: str) -> None:
     if status != OK:
         raise MQuantError(int(status), where)
@@ -119,6 +139,18 @@ def _check(status: int, where: str) -> None:
 def _dp(t) -> Optional[int]:
     """Device (or host) address of a torch tensor; None stays NULL."""
     return None if t is None else t.data_ptr()
+
+
+def _rows(t, what: str) -> None:
+    """A 2-D operand the ABI addresses through a leading dimension: unit stride along a row."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1) or (t.shape[0] > 1 and t.stride(0) < t.shape[1]):
+        raise MQuantError(ERR_BAD_SHAPE, f"{what}: expected a 2-D tensor with unit column stride")
+
+
+def _dense(t, what: str) -> None:
+    """An operand the ABI takes without a leading dimension."""
+    if t is not None and not t.is_contiguous():
+        raise MQuantError(ERR_BAD_SHAPE, f"{what}: expected a contiguous tensor")
 
 
 def _stream() -> Optional[int]:
@@ -151,6 +183,7 @@ def aifs_permute(x, perm_dev, out=None):
     T, K = x.shape
     if out is None:
         out = torch.empty((T, K), dtype=x.dtype, device=x.device)
+    _rows(x, "aifs_permute x"), _rows(out, "aifs_permute out"), _dense(perm_dev, "perm")
     _check(lib.mquant_aifs_permute(_dp(x), x.stride(0), _dp(out), out.stride(0), _dp(perm_dev),
                                    T, K, _stream()), "mquant_aifs_permute")
     return out
@@ -161,6 +194,7 @@ def aifs_remap_mask(mask, perm_dev, out=None):
     T = mask.shape[0]
     if out is None:
         out = torch.empty((T, T), dtype=torch.uint8, device=mask.device)
+    _dense(mask, "mask"), _dense(out, "mask_u"), _dense(perm_dev, "perm")
     _check(lib.mquant_aifs_remap_mask(_dp(mask), _dp(out), _dp(perm_dev), T, _stream()),
            "mquant_aifs_remap_mask")
     return out
@@ -173,6 +207,7 @@ def hadamard_quant_act(x, n_vis: int, s_vis: float, s_txt: float, had_block: int
     T = rows if T is None else T
     if out is None:
         out = torch.empty((T, K), dtype=torch.int8, device=x.device)
+    _rows(x, "hadamard_quant_act x"), _dense(out, "xq"), _dense(perm_dev, "perm")
     if act_bits is None:
         _check(lib.mquant_hadamard_quant_act(_dp(x), x.stride(0), _dp(perm_dev), _dp(out), T, K, n_vis,
                                              s_vis, s_txt, had_block, _stream()),
@@ -186,6 +221,7 @@ def hadamard_quant_act(x, n_vis: int, s_vis: float, s_txt: float, had_block: int
 
 def hadamard_absmax(x, had_block: int, absmax_dev):
     T, K = x.shape
+    _rows(x, "hadamard_absmax x")
     _check(lib.mquant_hadamard_absmax(_dp(x), x.stride(0), T, K, had_block, _dp(absmax_dev),
                                       _stream()), "mquant_hadamard_absmax")
     return absmax_dev
@@ -204,6 +240,7 @@ def w4_prepack(w_canonical, out=None):
     K = 2 * K2
     if out is None:
         out = torch.empty(w4_prepacked_bytes(N, K), dtype=torch.uint8, device=w_canonical.device)
+    _dense(w_canonical, "w_canonical"), _dense(out, "w_prepacked")
     _check(lib.mquant_w4_prepack(_dp(w_canonical), _dp(out), N, K, _stream()), "mquant_w4_prepack")
     return out
 
@@ -226,6 +263,7 @@ def w4a8_gemm(xq, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float, s_txt:
         if need:
             workspace = torch.empty(need, dtype=torch.uint8, device=xq.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _dense(xq, "xq"), _rows(out, "y"), _dense(acc_out, "acc_out"), _dense(w_scale, "w_scale")
     _check(lib.mquant_w4a8_gemm(_dp(xq), _dp(w_prepacked), _dp(w_scale), _dp(out), out.stride(0),
                                 _dp(acc_out), T, N, K, n_vis, s_vis, s_txt, _dp(workspace),
                                 ws_bytes, _stream()), "mquant_w4a8_gemm")
@@ -239,6 +277,7 @@ def hadamard_dynquant_act(x, had_block: int, perm_dev=None, out=None, row_scale=
         out = torch.empty((T, K), dtype=torch.int8, device=x.device)
     if row_scale is None:
         row_scale = torch.empty((T,), dtype=torch.float32, device=x.device)
+    _rows(x, "x"), _dense(out, "xq"), _dense(row_scale, "row_scale"), _dense(perm_dev, "perm")
     _check(lib.mquant_hadamard_dynquant_act(_dp(x), x.stride(0), _dp(perm_dev), _dp(out),
                                             _dp(row_scale), T, K, had_block, _stream()),
            "mquant_hadamard_dynquant_act")
@@ -256,6 +295,7 @@ def w4a8_gemm_rowscale(xq, w_prepacked, w_scale, row_scale, N: int, out=None, ac
         if need:
             workspace = torch.empty(need, dtype=torch.uint8, device=xq.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _dense(xq, "xq"), _rows(out, "y"), _dense(acc_out, "acc_out"), _dense(row_scale, "row_scale")
     _check(lib.mquant_w4a8_gemm_rowscale(_dp(xq), _dp(w_prepacked), _dp(w_scale), _dp(row_scale),
                                          _dp(out), out.stride(0), _dp(acc_out), T, N, K,
                                          _dp(workspace), ws_bytes, _stream()),
@@ -283,6 +323,7 @@ def w4a8_gemm_rms(xq, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float, s_
         if need:
             workspace = torch.empty(need, dtype=torch.uint8, device=xq.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _dense(xq, "xq"), _rows(out, "y"), _dense(acc_out, "acc_out"), _dense(split_w, "split_w")
     _check(lib.mquant_w4a8_gemm_rms(_dp(xq), _dp(w_prepacked), _dp(w_scale), _dp(out), out.stride(0),
                                     _dp(acc_out), T, N, K, n_vis, s_vis, s_txt, idx_p,
                                     _dp(split_w), sc_p, n_split, _dp(workspace),
@@ -304,6 +345,7 @@ def w4a8_linear_prefill(x, perm_dev, w_prepacked, w_scale, N: int, n_vis: int, s
     if out is None:
         out = torch.empty((T, N), dtype=torch.float16, device=x.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _rows(x, "x"), _rows(out, "y"), _dense(perm_dev, "perm"), _dense(w_scale, "w_scale")
     _check(lib.mquant_w4a8_linear_prefill(_dp(x), x.stride(0), _dp(perm_dev), _dp(w_prepacked),
                                           _dp(w_scale), _dp(out), out.stride(0), T, N, K, n_vis,
                                           s_vis, s_txt, had_block, _dp(workspace), ws_bytes,
@@ -342,20 +384,6 @@ def aifs_attention(q, k, v, pos_dev, n_q_heads: int, n_kv_heads: int, head_dim: 
                                      head_dim, _dp(workspace), ws_bytes, _stream()),
            "mquant_aifs_attention")
     return out
-
-
-def probe_mfma_i8(iters: int, data, sink) -> int:
-    """Launches the MFMA-only loop; returns the int8 operations it performs."""
-    _check(lib.mquant_probe_mfma_i8(iters, _dp(data), data.numel() * data.element_size(), _dp(sink),
-                                    _stream()), "mquant_probe_mfma_i8")
-    return int(lib.mquant_probe_mfma_i8_ops(iters))
-
-
-def probe_hbm_read(data, sink) -> int:
-    """Launches the read-only stream; returns the bytes it reads."""
-    n = data.numel() * data.element_size()
-    _check(lib.mquant_probe_hbm_read(_dp(data), n, _dp(sink), _stream()), "mquant_probe_hbm_read")
-    return n
 
 
 def w4a8_linear_decode(x, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float, s_txt: float,

@@ -4,7 +4,40 @@
 
 using namespace mquant;
 
-extern "C" int mquant_version(void) { return 100; }
+extern "C" int mquant_version(void) { return 200; }
+
+#ifndef MQUANT_BUILD_ID
+#define MQUANT_BUILD_ID "unknown"
+#endif
+extern "C" const char *mquant_build_id(void) { return MQUANT_BUILD_ID; }
+
+namespace mquant {
+TuneState &tune_state()
+{
+    static TuneState st;
+    return st;
+}
+}  // namespace mquant
+
+extern "C" int mquant_tune_set(int32_t key, int32_t value)
+{
+    TuneState &t = tune_state();
+    switch (key) {
+    case MQUANT_TUNE_GEMM_TILE:
+        if (value < -1 || value > 2) return MQUANT_ERR_BAD_SHAPE;
+        t.gemm_tile.store(value, std::memory_order_relaxed);
+        return MQUANT_OK;
+    case MQUANT_TUNE_GEMM_NOSPLIT:
+        if (value < 0 || value > 1) return MQUANT_ERR_BAD_SHAPE;
+        t.gemm_nosplit.store(value, std::memory_order_relaxed);
+        return MQUANT_OK;
+    case MQUANT_TUNE_G128_TILE:
+        if (value < -1 || value > 1) return MQUANT_ERR_BAD_SHAPE;
+        t.g128_tile.store(value, std::memory_order_relaxed);
+        return MQUANT_OK;
+    default: return MQUANT_ERR_BAD_SHAPE;
+    }
+}
 
 extern "C" const char *mquant_status_string(int status)
 {
@@ -110,6 +143,7 @@ extern "C" int mquant_aifs_permute(const void *x, int64_t ldx, void *x_u, int64_
     if (T == 0 || K == 0) return MQUANT_OK;
     if (!x || !x_u || !perm) return MQUANT_ERR_NULL;
     if (ldx < K || ldxu < K) return MQUANT_ERR_BAD_SHAPE;
+    if (x == x_u) return MQUANT_ERR_BAD_SHAPE;            // a gather cannot run in place
     if (K % 8 != 0) return MQUANT_ERR_UNSUPPORTED;
     if (ldx % 8 != 0 || ldxu % 8 != 0 || !aligned_to(x, 16) || !aligned_to(x_u, 16))
         return MQUANT_ERR_ALIGNMENT;

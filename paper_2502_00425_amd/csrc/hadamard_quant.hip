@@ -182,6 +182,20 @@ extern "C" int mquant_hadamard_quant_act_bits(const void *x, int64_t ldx, const 
                          static_cast<hipStream_t>(stream), act_bits);
 }
 
+// Eq. (2): s = max|x_rot| / (2^(b-1) - 1), x_rot = u / sqrt(B); double, one rounding.
+extern "C" int mquant_static_scale_from_absmax(float absmax_u, int32_t had_block, int32_t act_bits,
+                                               float *scale)
+{
+    if (!scale) return MQUANT_ERR_NULL;
+    if (had_block < 1 || had_block > 1024 || (had_block & (had_block - 1)) != 0)
+        return MQUANT_ERR_UNSUPPORTED;
+    if (act_bits < 2 || act_bits > 8) return MQUANT_ERR_UNSUPPORTED;
+    if (!(absmax_u >= 0.0f) || !isfinite(absmax_u)) return MQUANT_ERR_BAD_SHAPE;
+    const double q_max = static_cast<double>((1 << (act_bits - 1)) - 1);
+    *scale = static_cast<float>(static_cast<double>(absmax_u) / sqrt(static_cast<double>(had_block)) / q_max);
+    return MQUANT_OK;
+}
+
 extern "C" int mquant_hadamard_absmax(const void *x, int64_t ldx, int32_t T, int32_t K,
                                       int32_t had_block, float *absmax, mquant_stream_t stream)
 {

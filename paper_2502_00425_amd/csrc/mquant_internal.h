@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <stdint.h>
@@ -36,6 +37,14 @@ static inline int launch_status()
     if (getenv("MQUANT_DEBUG")) fprintf(stderr, "mquant: HIP error %d: %s\n", (int)e, hipGetErrorString(e));
     return MQUANT_ERR_HIP;
 }
+
+// Process-wide overrides of kernel choices (mquant_tune_set); -1 / 0 = cost model.
+struct TuneState {
+    std::atomic<int32_t> gemm_tile{-1};
+    std::atomic<int32_t> gemm_nosplit{0};
+    std::atomic<int32_t> g128_tile{-1};
+};
+TuneState &tune_state();
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 

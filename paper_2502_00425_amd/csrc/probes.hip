@@ -1,10 +1,14 @@
-// Measurement probes (not part of the method): what the chip attains on the two
-// resources the hot path is bound by, so that a kernel's rate can be set against
-// the attainable figure as well as the published one.
+// Measurement probes of the benchmark (not part of the method and not part of
+// libmquant: built into their own shared object, libmquant_probes.so): what the
+// chip attains on the resources the hot path is bound by, so that a kernel's rate
+// can be set against the attainable figure as well as the published one.
 //   - an MFMA-only loop of v_mfma_i32_32x32x32_i8 on caller-supplied operand data
 //     (the matrix clock of this chip depends on the data: constant operands run at
 //     the published rate, random int8 operands about 30 % below it);
-//   - a read-only stream over a buffer (16 bytes per lane, non-temporal).
+//   - a read-only stream over a buffer (16 bytes per lane, non-temporal);
+//   - an empty kernel (the launch-to-launch floor of back-to-back kernels).
+#include "probes.h"
+
 #include "mquant_internal.h"
 
 using namespace mquant;
@@ -54,17 +58,19 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const v4u *__restrict__
     if ((x[0] ^ x[1] ^ x[2] ^ x[3]) == 0x9e3779b9u) sink[0] = x[0];
 }
 
+__global__ void probe_empty_kernel() {}
+
 constexpr int kProbeGroups = 1024;                    // 4 per CU, 4 waves each: 4 waves per SIMD
 
 }  // namespace
 
-extern "C" int64_t mquant_probe_mfma_i8_ops(int32_t iters)
+extern "C" int64_t mqprobe_mfma_i8_ops(int32_t iters)
 {
     if (iters < 0) return MQUANT_ERR_BAD_SHAPE;
     return static_cast<int64_t>(iters) * 8 * (2LL * 32 * 32 * 32) * 4 * kProbeGroups;
 }
 
-extern "C" int mquant_probe_mfma_i8(int32_t iters, const void *data, int64_t data_bytes, int32_t *sink,
+extern "C" int mqprobe_mfma_i8(int32_t iters, const void *data, int64_t data_bytes, int32_t *sink,
                                     mquant_stream_t stream)
 {
     if (iters < 0 || data_bytes < 4096) return MQUANT_ERR_BAD_SHAPE;
@@ -77,7 +83,7 @@ extern "C" int mquant_probe_mfma_i8(int32_t iters, const void *data, int64_t dat
     return launch_status();
 }
 
-extern "C" int mquant_probe_hbm_read(const void *data, int64_t data_bytes, uint32_t *sink,
+extern "C" int mqprobe_hbm_read(const void *data, int64_t data_bytes, uint32_t *sink,
                                      mquant_stream_t stream)
 {
     if (data_bytes < 0) return MQUANT_ERR_BAD_SHAPE;
@@ -86,5 +92,13 @@ extern "C" int mquant_probe_hbm_read(const void *data, int64_t data_bytes, uint3
     if (!aligned_to(data, 16)) return MQUANT_ERR_ALIGNMENT;
     MQ_LAUNCH(probe_read_kernel, dim3(8 * 256), dim3(256), 0, static_cast<hipStream_t>(stream),
               static_cast<const v4u *>(data), data_bytes / 16, sink);
+    return launch_status();
+}
+
+extern "C" int mqprobe_empty(int32_t groups, int32_t threads, mquant_stream_t stream)
+{
+    if (groups < 1 || threads < 64 || threads > 1024 || threads % 64 != 0) return MQUANT_ERR_BAD_SHAPE;
+    MQ_LAUNCH(probe_empty_kernel, dim3(static_cast<unsigned>(groups)), dim3(static_cast<unsigned>(threads)), 0,
+              static_cast<hipStream_t>(stream));
     return launch_status();
 }

@@ -1043,9 +1043,8 @@ int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void
         return MQUANT_OK;
     }
     int splits = plan_splits(T, N, K);
-    int force_tile = -1;
-    if (const char *e = getenv("MQUANT_TUNE_TILE")) { if (*e) force_tile = atoi(e); }
-    if (const char *e = getenv("MQUANT_TUNE_NOSPLIT")) { if (atoi(e)) splits = 1; }
+    const int force_tile = tune_state().gemm_tile.load(std::memory_order_relaxed);
+    if (tune_state().gemm_nosplit.load(std::memory_order_relaxed)) splits = 1;
     if (splits > 1) {
         const int64_t need = static_cast<int64_t>(splits) * T * N * 4;
         if (!workspace || workspace_bytes < need) return MQUANT_ERR_WORKSPACE;

@@ -550,7 +550,8 @@ extern "C" int mquant_w4g128_gemm(const void *x, int64_t ldx, const uint8_t *wp,
     const double c128 = static_cast<double>(ceil_div(ceil_div(T, 128) * ceil_div(N, 256), kNumCU)) * 128.0;
     const double c96 = static_cast<double>(ceil_div(ceil_div(T, 96) * ceil_div(N, 256), kNumCU)) * 96.0 / 0.9;
     int tile = c96 < c128 ? 1 : 0;
-    if (const char *e = getenv("MQUANT_TUNE_G128_TILE")) { if (*e) tile = atoi(e); }
+    const int32_t forced = tune_state().g128_tile.load(std::memory_order_relaxed);
+    if (forced >= 0) tile = forced;
     if (tile == 1) return launch_g128<96, 256, 1, 8>(xh, ldx, wp, yh, ldy, T, N, K, st);
     return launch_g128<128, 256, 1, 8>(xh, ldx, wp, yh, ldy, T, N, K, st);
 }

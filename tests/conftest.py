@@ -10,11 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    # The tests load the library that is built; only when there is none do they build it
-    # (hipcc cross-compiles without a GPU).
+    # The tests load the library that is built, unless it was built from other sources than
+    # the ones in the tree (content hash): then it is rebuilt first (hipcc cross-compiles
+    # without a GPU), so an edited kernel is never tested against an older binary.
     from paper_2502_00425_amd import build as hip_build
-    if not os.path.exists(hip_build.LIB):
-        hip_build.build(force=True)
+    hip_build.ensure_fresh()
 
 
 @pytest.fixture(scope="session")

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     raw = ctypes.CDLL(mq.LIB_PATH)
     for n in names:
         assert hasattr(raw, n), n
-    assert mq.version() >= 100
+    assert mq.version() >= 200
     assert mq.status_string(0) == "ok"
     for code in range(-6, 0):
         assert mq.status_string(code) not in ("ok", "unknown status")
@@ -72,11 +72,12 @@ def test_device_entry_points_validate_before_launch():
     P = 0x1000                 # 16-byte (and 256-byte) aligned fake address
     L = mq.lib
     # permute
-    assert L.mquant_aifs_permute(None, 64, P, 64, P, 4, 64, None) == mq.ERR_NULL
-    assert L.mquant_aifs_permute(P, 32, P, 64, P, 4, 64, None) == mq.ERR_BAD_SHAPE
-    assert L.mquant_aifs_permute(P, 64, P, 64, P, 4, 60, None) == mq.ERR_UNSUPPORTED
-    assert L.mquant_aifs_permute(P + 2, 64, P, 64, P, 4, 64, None) == mq.ERR_ALIGNMENT
-    assert L.mquant_aifs_permute(P, 64, P, 64, P, -1, 64, None) == mq.ERR_BAD_SHAPE
+    Q = 0x2000
+    assert L.mquant_aifs_permute(None, 64, Q, 64, P, 4, 64, None) == mq.ERR_NULL
+    assert L.mquant_aifs_permute(P, 32, Q, 64, P, 4, 64, None) == mq.ERR_BAD_SHAPE
+    assert L.mquant_aifs_permute(P, 64, Q, 64, P, 4, 60, None) == mq.ERR_UNSUPPORTED
+    assert L.mquant_aifs_permute(P + 2, 64, Q, 64, P, 4, 64, None) == mq.ERR_ALIGNMENT
+    assert L.mquant_aifs_permute(P, 64, Q, 64, P, -1, 64, None) == mq.ERR_BAD_SHAPE
     assert L.mquant_aifs_permute(None, 0, None, 0, None, 0, 64, None) == mq.OK       # empty
     # mask
     assert L.mquant_aifs_remap_mask(None, P, P, 8, None) == mq.ERR_NULL
@@ -196,10 +197,86 @@ def test_widened_entry_points_validate_before_launch():
     assert att(None, 3584, None, 512, None, 512, None, 3584, None, 0, 28, 4, 128, None, 0, None) == mq.OK
 
 
-def test_static_scale_host_formula_matches_oracle():
+def test_static_scale_is_computed_by_the_library_and_matches_the_oracle():
+    """Eq. (2)'s scale lives behind the C ABI (a host function), not in the Python package."""
     import paper_2502_00425_amd as pkg
-    for absmax, B in [(1234.5, 512), (7.0, 128), (1e-3, 1), (65504.0 * 512, 512)]:
-        assert np.float32(pkg.static_scale_from_absmax(absmax, B)) == orc.static_scale_from_absmax(absmax, B)
+    assert not hasattr(pkg, "static_scale_from_absmax")
+    for absmax, B in [(1234.5, 512), (7.0, 128), (1e-3, 1), (65504.0 * 512, 512), (0.0, 16)]:
+        assert np.float32(mq.static_scale_from_absmax(absmax, B)) == orc.static_scale_from_absmax(absmax, B)
+        for bits in (2, 4, 8):
+            assert (np.float32(mq.static_scale_from_absmax(absmax, B, bits))
+                    == orc.static_scale_from_absmax_bits(absmax, B, bits))
+    # a hand case: absmax of the unnormalised rotation 254 * sqrt(16) -> s = 254 / 127 = 2
+    assert mq.static_scale_from_absmax(254.0 * 4.0, 16) == 2.0
+    out = ctypes.c_float(0.0)
+    po = ctypes.cast(ctypes.byref(out), ctypes.c_void_p)
+    f = mq.lib.mquant_static_scale_from_absmax
+    assert f(1.0, 512, 8, None) == mq.ERR_NULL
+    assert f(1.0, 96, 8, po) == mq.ERR_UNSUPPORTED
+    assert f(1.0, 2048, 8, po) == mq.ERR_UNSUPPORTED
+    assert f(1.0, 512, 9, po) == mq.ERR_UNSUPPORTED
+    assert f(1.0, 512, 1, po) == mq.ERR_UNSUPPORTED
+    assert f(-1.0, 512, 8, po) == mq.ERR_BAD_SHAPE
+    assert f(float("nan"), 512, 8, po) == mq.ERR_BAD_SHAPE
+    assert f(float("inf"), 512, 8, po) == mq.ERR_BAD_SHAPE
+
+
+def test_tune_hook_validates_and_resets():
+    f = mq.lib.mquant_tune_set
+    assert f(99, 0) == mq.ERR_BAD_SHAPE
+    assert f(mq.TUNE_GEMM_TILE, 3) == mq.ERR_BAD_SHAPE
+    assert f(mq.TUNE_GEMM_TILE, -2) == mq.ERR_BAD_SHAPE
+    assert f(mq.TUNE_GEMM_NOSPLIT, 2) == mq.ERR_BAD_SHAPE
+    assert f(mq.TUNE_G128_TILE, 2) == mq.ERR_BAD_SHAPE
+    # NOSPLIT changes the workspace a long-K, few-tile shape asks for; setting it back restores it
+    base = mq.w4a8_workspace_bytes(300, 520, 8192)
+    assert base > 0
+    for key, val, back in ((mq.TUNE_GEMM_TILE, 2, -1), (mq.TUNE_GEMM_NOSPLIT, 1, 0), (mq.TUNE_G128_TILE, 1, -1)):
+        assert f(key, val) == mq.OK
+        assert f(key, back) == mq.OK
+    assert mq.w4a8_workspace_bytes(300, 520, 8192) == base
+
+
+def test_loaded_library_was_built_from_the_sources_in_the_tree():
+    """A stale binary must not pass for the code under test: the hash compiled into the
+    library equals the hash of the sources, headers and flags now in the tree."""
+    from paper_2502_00425_amd import build as hip_build
+    assert mq.build_id() == hip_build.source_hash()
+    assert not hip_build.is_stale()
+
+
+def test_probe_library_is_separate_from_the_product_abi():
+    raw = ctypes.CDLL(mq.LIB_PATH)
+    for n in ("mquant_probe_mfma_i8", "mquant_probe_hbm_read", "mqprobe_mfma_i8", "mqprobe_empty"):
+        assert not hasattr(raw, n), n
+    from paper_2502_00425_amd import probes
+    for n in probes.EXPORTS:
+        assert hasattr(probes.lib, n), n
+    assert probes.lib.mqprobe_mfma_i8_ops(10) == 10 * 8 * 65536 * 4 * 1024
+    assert probes.lib.mqprobe_mfma_i8_ops(-1) == mq.ERR_BAD_SHAPE
+    assert probes.lib.mqprobe_mfma_i8(-1, 0x1000, 1 << 16, 0x1000, None) == mq.ERR_BAD_SHAPE
+    assert probes.lib.mqprobe_hbm_read(None, 16, 0x1000, None) == mq.ERR_NULL
+    assert probes.lib.mqprobe_empty(0, 256, None) == mq.ERR_BAD_SHAPE
+    assert probes.lib.mqprobe_empty(1, 100, None) == mq.ERR_BAD_SHAPE
+
+
+def test_binding_rejects_operands_the_abi_cannot_address():
+    """The ABI has no leading dimension for xq, the weights, the index vector or the mask:
+    the binding refuses non-contiguous tensors there instead of passing a wrong pointer."""
+    torch = pytest.importorskip("torch")
+    xq = torch.zeros((8, 256), dtype=torch.int8)[:, :128]
+    wp = torch.zeros(mq.w4_prepacked_bytes(32, 128), dtype=torch.uint8)
+    ws = torch.ones(32, dtype=torch.float16)
+    with pytest.raises(mq.MQuantError):
+        mq.w4a8_gemm(xq, wp, ws, 32, 0, 1.0, 1.0, out=torch.zeros((8, 32), dtype=torch.float16))
+    x = torch.zeros((8, 64), dtype=torch.float16)
+    with pytest.raises(mq.MQuantError):
+        mq.aifs_permute(x.t(), torch.zeros(64, dtype=torch.int32))
+    with pytest.raises(mq.MQuantError):
+        mq.aifs_remap_mask(torch.zeros((8, 16), dtype=torch.uint8)[:, :8], torch.zeros(8, dtype=torch.int32))
+    # in-place gather is rejected by the library itself
+    P = 0x1000
+    assert mq.lib.mquant_aifs_permute(P, 64, P, 64, P, 4, 64, None) == mq.ERR_BAD_SHAPE
 
 
 def test_header_is_plain_c():

@@ -24,6 +24,19 @@ def mq():
     return binding
 
 
+@pytest.fixture
+def forced_tile(mq):
+    """Sets a tuning override of the library and puts the cost model back afterwards."""
+    keys = []
+
+    def force(key, value):
+        mq.tune_set(key, value)
+        keys.append(key)
+    yield force
+    for key in keys:
+        mq.tune_set(key, 0 if key == mq.TUNE_GEMM_NOSPLIT else -1)
+
+
 def say(msg):
     print(f"[parity] {msg}", flush=True)
     sys.stdout.flush()
@@ -443,14 +456,15 @@ def test_config4_72b_T16384(mq, proj):
 
 
 def test_measurement_probes_run(mq):
-    """The attainable-peak probes of the benchmark: launch, finish, report their work."""
+    """The attainable-peak probes of the benchmark (their own library): launch, finish,
+    report their work."""
+    from paper_2502_00425_amd import probes
     data = torch.randint(0, 256, (1 << 16,), dtype=torch.uint8, device="cuda")
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
-    assert mq.probe_mfma_i8(10, data, sink) == 10 * 8 * 65536 * 4 * 1024
-    assert mq.probe_hbm_read(data, sink) == 1 << 16
+    assert probes.mfma_i8(10, data, sink) == 10 * 8 * 65536 * 4 * 1024
+    assert probes.hbm_read(data, sink) == 1 << 16
+    probes.empty(256, 256)
     torch.cuda.synchronize()
-    assert mq.lib.mquant_probe_mfma_i8(-1, data.data_ptr(), 1 << 16, sink.data_ptr(), None) == mq.ERR_BAD_SHAPE
-    assert mq.lib.mquant_probe_hbm_read(None, 16, sink.data_ptr(), None) == mq.ERR_NULL
 
 
 @pytest.mark.parametrize("T,N,K,B", [(1, 200, 896, 128), (1, 3584, 3584, 512), (4, 512, 3584, 512),
@@ -572,11 +586,11 @@ def test_prefill_step_as_hip_graph_replays_match_plain_launches(mq):
 
 
 @pytest.mark.parametrize("tile,name", [(0, "256x256"), (1, "128x256"), (2, "192x128")])
-def test_every_gemm_tile_on_ragged_shapes(mq, tile, name, monkeypatch):
+def test_every_gemm_tile_on_ragged_shapes(mq, tile, name, forced_tile):
     """The dispatcher picks a tile from a cost model; this forces each compiled tile in turn
-    (a tuning hook of the library) so that all of them see ragged T and N, one k-block and
+    (the tuning hook of the library) so that all of them see ragged T and N, one k-block and
     many, whatever the model prefers."""
-    monkeypatch.setenv("MQUANT_TUNE_TILE", str(tile))
+    forced_tile(mq.TUNE_GEMM_TILE, tile)
     rng = np.random.default_rng(900 + tile)
     for T, N, K in [(33, 40, 128), (200, 136, 384), (450, 520, 1024), (577, 300, 2048)]:
         say(f"tile {name} T={T} N={N} K={K}")

@@ -147,19 +147,22 @@ def test_argument_errors_and_empty_inputs(mq):
 
 
 @pytest.mark.parametrize("tile", [0, 1])
-def test_both_gemm_tiles_on_ragged_shapes(mq, tile, monkeypatch):
-    """The dispatcher picks 128x256 or 96x256 from a cost model; force each (a tuning hook of
+def test_both_gemm_tiles_on_ragged_shapes(mq, tile):
+    """The dispatcher picks 128x256 or 96x256 from a cost model; force each (the tuning hook of
     the library) so that both see ragged shapes whatever the model prefers."""
-    monkeypatch.setenv("MQUANT_TUNE_G128_TILE", str(tile))
-    rng = np.random.default_rng(70 + tile)
-    for T, N, K in [(65, 264, 128), (200, 300, 384), (410, 1000, 640)]:
-        wq, sc = make_weight(rng, N, K)
-        x = (rng.standard_normal((T, K)) * 1.5).astype(np.float16)
-        ref, mag = orc.w4g128_linear(x, wq, sc)
-        wp = mq.w4g128_prepack(dev(pack_int4(wq)), dev(sc))
-        say(f"tile {tile} T={T} N={N} K={K}")
-        y = mq.w4g128_gemm(dev(x), wp, N).cpu().numpy()
-        check(y, ref, mag, f"w4g128 tile {tile} {(T, N, K)}")
+    mq.tune_set(mq.TUNE_G128_TILE, tile)
+    try:
+        rng = np.random.default_rng(70 + tile)
+        for T, N, K in [(65, 264, 128), (200, 300, 384), (410, 1000, 640)]:
+            wq, sc = make_weight(rng, N, K)
+            x = (rng.standard_normal((T, K)) * 1.5).astype(np.float16)
+            ref, mag = orc.w4g128_linear(x, wq, sc)
+            wp = mq.w4g128_prepack(dev(pack_int4(wq)), dev(sc))
+            say(f"tile {tile} T={T} N={N} K={K}")
+            y = mq.w4g128_gemm(dev(x), wp, N).cpu().numpy()
+            check(y, ref, mag, f"w4g128 tile {tile} {(T, N, K)}")
+    finally:
+        mq.tune_set(mq.TUNE_G128_TILE, -1)
 
 
 def test_output_beyond_2_31_elements(mq):
