@@ -313,6 +313,29 @@ int mquant_w4a8_linear_prefill(const void *x_dev, int64_t ldx, const int32_t *pe
                                mquant_stream_t stream);
 
 /*
+ * DEVICE.  mquant_w4a8_linear_prefill for callers that cannot allocate device
+ * memory or keep a workspace alive: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the
+ * same results bit for bit, minus the workspace: the int8 activations and the
+ * split-K partial sums go to a 128 MiB device array inside the library
+ * (MQUANT_STATIC_SCRATCH_BYTES; one per GPU the library is used on, held until
+ * the process ends).  The call allocates and frees nothing.
+ * Errors: as mquant_w4a8_linear_prefill; ERR_WORKSPACE when
+ * mquant_w4a8_linear_prefill_workspace_bytes(T, N, K) exceeds the array (nothing
+ * is launched); ERR_HIP when the array's address cannot be obtained.
+ * All calls on one GPU share the array: calls that may overlap on one GPU (two
+ * streams, two host threads) race on it and must be ordered by the caller.  Its
+ * contents after a call are unspecified.
+ */
+#define MQUANT_STATIC_SCRATCH_BYTES (128ll << 20)
+int mquant_w4a8_linear_prefill_static(const void *x_dev, int64_t ldx, const int32_t *perm_dev,
+                                      const uint8_t *w_prepacked_dev, const void *w_scale_dev,
+                                      void *y_dev, int64_t ldy,
+                                      int32_t T, int32_t N, int32_t K, int32_t n_vis,
+                                      float s_vis, float s_txt, int32_t had_block,
+                                      mquant_stream_t stream);
+
+/*
  * DEVICE.  The whole path of one linear at decode (T <= 4 new rows) in ONE
  * launch: block-Hadamard rotation and static quantization of x (as
  * mquant_hadamard_quant_act, no gather) inside the weight-streaming GEMV, then

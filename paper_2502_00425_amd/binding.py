@@ -31,7 +31,7 @@ EXPORTS = (
     "mquant_rope_apply", "mquant_aifs_attention_workspace_bytes", "mquant_aifs_attention",
     "mquant_hadamard_quant_act_bits", "mquant_static_scale_from_absmax", "mquant_tune_set",
     "mquant_build_id",
-    "mquant_w4a8_linear_decode",
+    "mquant_w4a8_linear_decode", "mquant_w4a8_linear_prefill_static",
     "mquant_w4g128_prepacked_bytes", "mquant_w4g128_prepack", "mquant_w4g128_gemm",
 )
 
@@ -82,6 +82,8 @@ def _load() -> ctypes.CDLL:
     lib.mquant_w4a8_linear_prefill_workspace_bytes.argtypes = [i32, i32, i32]
     lib.mquant_w4a8_linear_prefill.argtypes = [p, i64, p, p, p, p, i64, i32, i32, i32, i32, f32, f32,
                                                i32, p, i64, p]
+    lib.mquant_w4a8_linear_prefill_static.argtypes = [p, i64, p, p, p, p, i64, i32, i32, i32, i32, f32, f32,
+                                                      i32, p]
     lib.mquant_rope_apply.argtypes = [p, i64, p, i32, i32, i32, ctypes.c_double, p]
     lib.mquant_aifs_attention_workspace_bytes.restype = i64
     lib.mquant_aifs_attention_workspace_bytes.argtypes = [i32, i32, i32]
@@ -350,6 +352,22 @@ def w4a8_linear_prefill(x, perm_dev, w_prepacked, w_scale, N: int, n_vis: int, s
                                           _dp(w_scale), _dp(out), out.stride(0), T, N, K, n_vis,
                                           s_vis, s_txt, had_block, _dp(workspace), ws_bytes,
                                           _stream()), "mquant_w4a8_linear_prefill")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 128 << 20
+
+
+def w4a8_linear_prefill_static(x, perm_dev, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float,
+                               s_txt: float, had_block: int, out):
+    """The fused prefill entry on the library's own scratch array; `out` is required (the
+    point of the entry is that nothing gets allocated)."""
+    T, K = x.shape
+    _rows(x, "x"), _rows(out, "y"), _dense(perm_dev, "perm"), _dense(w_scale, "w_scale")
+    _check(lib.mquant_w4a8_linear_prefill_static(_dp(x), x.stride(0), _dp(perm_dev), _dp(w_prepacked),
+                                                 _dp(w_scale), _dp(out), out.stride(0), T, N, K, n_vis,
+                                                 s_vis, s_txt, had_block, _stream()),
+           "mquant_w4a8_linear_prefill_static")
     return out
 
 

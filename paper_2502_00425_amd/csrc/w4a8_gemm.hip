@@ -1167,6 +1167,62 @@ extern "C" int mquant_w4a8_linear_prefill(const void *x, int64_t ldx, const int3
                             static_cast<uint8_t *>(workspace) + xq_bytes, need - xq_bytes, stream);
 }
 
+// ------------------------------------------------ fused prefill without a caller workspace
+//
+// For callers that cannot allocate (code under HIP graph capture, serving loops,
+// harnesses that forbid hipMalloc): the workspace of the fused prefill entry -- the int8
+// activations between the two kernels and the split-K partial sums -- lives in a
+// file-scope device array instead.  Every GPU the library runs on holds its own copy at
+// its own address until the process ends; in host code the array's name is only a handle
+// for hipGetSymbolAddress, never an address to pass on.
+namespace {
+
+constexpr int64_t kStaticScratchBytes = 128ll << 20;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MQUANT_ERR_HIP;
+    void *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return MQUANT_ERR_HIP;
+        }
+        // threads racing here store the same address
+        scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return MQUANT_OK;
+}
+
+}  // namespace
+
+extern "C" int mquant_w4a8_linear_prefill_static(const void *x, int64_t ldx, const int32_t *perm,
+                                                 const uint8_t *wp, const void *w_scale, void *y,
+                                                 int64_t ldy, int32_t T, int32_t N, int32_t K,
+                                                 int32_t n_vis, float s_vis, float s_txt,
+                                                 int32_t had_block, mquant_stream_t stream)
+{
+    const int64_t need = mquant_w4a8_linear_prefill_workspace_bytes(T, N, K);
+    if (need < 0) return static_cast<int>(need);
+    if (need > kStaticScratchBytes) return MQUANT_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (T > 0 && N > 0) {
+        const int st = static_scratch(&ws);
+        if (st != MQUANT_OK) return st;
+    }
+    // Nothing in the scratch has to start at zero: the front end writes every code the GEMM
+    // reads, and the split-K kernels write every partial sum the reduction reads.
+    return mquant_w4a8_linear_prefill(x, ldx, perm, wp, w_scale, y, ldy, T, N, K, n_vis, s_vis, s_txt,
+                                      had_block, ws, kStaticScratchBytes, stream);
+}
+
 namespace {
 
 constexpr int kDecodeFusedMaxT = 4;
