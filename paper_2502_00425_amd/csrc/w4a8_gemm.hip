@@ -97,6 +97,17 @@ __device__ __forceinline__ v4i as_v4i(const uint4 u)
 // Row of the 32x32 MFMA result held in accumulator register r by k-group g.
 __device__ __forceinline__ int acc_row(int r, int g) { return (r >> 2) * 8 + g * 4 + (r & 3); }
 
+// fp16 round-to-nearest-even of an fp32 value that has ALREADY been rounded to fp32.  The
+// empty asm keeps the compiler from merging the last fp32 multiply of the dequantisation
+// with the conversion into one v_fma_mixlo_f16, which rounds the exact product once, straight
+// to fp16: the defined result is the fp32 product rounded again (about 6 outputs in 10^5
+// differ by one fp16 ulp otherwise).
+__device__ __forceinline__ __half half_of_rounded_f32(float v)
+{
+    asm("" : "+v"(v));
+    return __float2half_rn(v);
+}
+
 // Everything the dequantising epilogue needs besides the accumulator and the
 // per-channel weight scale.  Activation scale of a row: the two static modality
 // scales split at row n_vis (Eq. (3)), or, for the per-token dynamic baseline,
@@ -155,7 +166,7 @@ __device__ __forceinline__ void store_out(int32_t acc16, int32_t row, int32_t n,
     const int32_t acc = acc16 >> 4;                       // exact: acc16 = 16 * acc
     const float s_row = ep.scale_of<EPI>(row);
     y[static_cast<int64_t>(row) * ldy + n] =
-        __float2half_rn(ep.dequant<EPI>(acc, s_row, row, n, N, ws));
+        half_of_rounded_f32(ep.dequant<EPI>(acc, s_row, row, n, N, ws));
     if (acc_out) acc_out[static_cast<int64_t>(row) * N + n] = acc;
 }
 
@@ -518,7 +529,7 @@ __global__ __launch_bounds__(WM *WN * 64, STAGES == 2 ? 4 : 2) void w4a8_gemm_ke
                 n = n < N ? n : N - 1;                             // only read by the split path
                 const float v = ep.dequant<EPI>(a, s_row, row_in, n, N, ws[nt]);
                 *reinterpret_cast<__half *>(patch + rl * ROWB + (nt * 32 + l32) * 2) =
-                    __float2half_rn(v);
+                    half_of_rounded_f32(v);
             }
         }
 #pragma unroll
@@ -580,7 +591,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(
         }
         __half h[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) h[e] = __float2half_rn(v[e]);
+        for (int e = 0; e < 4; ++e) h[e] = half_of_rounded_f32(v[e]);
         __half *dst = y + static_cast<int64_t>(row) * ldy + n;
         if ((reinterpret_cast<uintptr_t>(dst) & 7) == 0) {
             *reinterpret_cast<uint2 *>(dst) = *reinterpret_cast<const uint2 *>(h);
