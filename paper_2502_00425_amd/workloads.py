@@ -127,3 +127,41 @@ def make_linear_inputs(wl: Workload, proj: str, *, want_calib: bool = True,
         out["calib_vis"] = draw_activations(r_cv, CALIB_ROWS, K, np.ones(CALIB_ROWS, dtype=bool))
         out["calib_txt"] = draw_activations(r_ct, CALIB_ROWS, K, np.zeros(CALIB_ROWS, dtype=bool))
     return out
+
+
+def device_linear_inputs(torch, wl: Workload, proj: str, *, want_x: bool = True) -> dict:
+    """The same recipe drawn on the GPU with torch's seeded generator: benchmark inputs of the
+    large configurations, where a host draw plus upload would dominate the run.  Distributions,
+    shapes and token layout are those of make_linear_inputs; the values are another draw."""
+    names: List[str] = list(wl.projections)
+    K, N = wl.projections[proj]
+    T = wl.T
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed_for(wl.cfg, names.index(proj)) + 7_000_000)
+    gain = torch.full((K,), VIS_SIGMA, dtype=torch.float32, device="cuda")
+    for c in OUTLIER_CHANNELS:
+        if c < K:
+            gain[c] *= OUTLIER_GAIN
+    is_vis = torch.from_numpy(_is_visual(T, wl.vis_spans)).cuda()
+
+    def draw(rows, vis_mask):
+        out = torch.empty((rows, K), dtype=torch.float16, device="cuda")
+        for r0 in range(0, rows, 2048):                       # slabs: no fp32 temporary of the whole matrix
+            r1 = min(r0 + 2048, rows)
+            blk = torch.randn((r1 - r0, K), dtype=torch.float32, device="cuda", generator=gen)
+            m = vis_mask[r0:r1]
+            blk[m] *= gain
+            out[r0:r1] = blk.to(torch.float16)
+        return out
+
+    ones = torch.ones(CALIB_ROWS, dtype=torch.bool, device="cuda")
+    res = {
+        "T": T, "K": K, "N": N, "had_block": wl.had_block, "vis_spans": tuple(wl.vis_spans),
+        "w_packed": torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device="cuda", generator=gen),
+        "w_scale": (torch.rand(N, device="cuda", generator=gen) * 0.015 + 0.005).to(torch.float16),
+        "calib_vis": draw(CALIB_ROWS, ones),
+        "calib_txt": draw(CALIB_ROWS, ~ones),
+    }
+    if want_x:
+        res["x"] = draw(T, is_vis)
+    return res
