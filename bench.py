@@ -632,6 +632,32 @@ def bench_decode(b):
                 for proj, (K, N, wp, ws) in layer.items():
                     mq.w4a8_gemm(xq[K], wp, ws, N, 0, s_txt, s_txt, out=ys[N])
 
+        def gemv_grouped_pass():
+            # four launches per layer through the grouped entry: q/k/v and gate/up keep their own
+            # weight buffers and outputs (nothing is concatenated), o and down are groups of one
+            for layer in layers:
+                mq.w4a8_gemv_grouped(xq[3584], [(layer[p][2], layer[p][3], layer[p][1], ys_multi[i][layer[p][1]])
+                                                for i, p in enumerate(("q", "k", "v"))], 0, s_txt, s_txt)
+                mq.w4a8_gemv_grouped(xq[3584], [(layer["o"][2], layer["o"][3], 3584, ys[3584])], 0, s_txt, s_txt)
+                mq.w4a8_gemv_grouped(xq[3584], [(layer[p][2], layer[p][3], layer[p][1], ys_multi[i][layer[p][1]])
+                                                for i, p in enumerate(("gate", "up"))], 0, s_txt, s_txt)
+                mq.w4a8_gemv_grouped(xq[18944], [(layer["down"][2], layer["down"][3], 3584, ys[3584])], 0, s_txt, s_txt)
+
+        def layer_grouped_pass():
+            # a decoder layer as deployed with the grouped entry: one rotate+quant per distinct
+            # input (four per layer: attention input, attention output, MLP input, MLP hidden)
+            for layer in layers:
+                mq.hadamard_quant_act(xs[3584], 0, s_txt, s_txt, 512, out=xq[3584])
+                mq.w4a8_gemv_grouped(xq[3584], [(layer[p][2], layer[p][3], layer[p][1], ys_multi[i][layer[p][1]])
+                                                for i, p in enumerate(("q", "k", "v"))], 0, s_txt, s_txt)
+                mq.hadamard_quant_act(xs[3584], 0, s_txt, s_txt, 512, out=xq[3584])
+                mq.w4a8_gemv_grouped(xq[3584], [(layer["o"][2], layer["o"][3], 3584, ys[3584])], 0, s_txt, s_txt)
+                mq.hadamard_quant_act(xs[3584], 0, s_txt, s_txt, 512, out=xq[3584])
+                mq.w4a8_gemv_grouped(xq[3584], [(layer[p][2], layer[p][3], layer[p][1], ys_multi[i][layer[p][1]])
+                                                for i, p in enumerate(("gate", "up"))], 0, s_txt, s_txt)
+                mq.hadamard_quant_act(xs[18944], 0, s_txt, s_txt, 512, out=xq[18944])
+                mq.w4a8_gemv_grouped(xq[18944], [(layer["down"][2], layer["down"][3], 3584, ys[3584])], 0, s_txt, s_txt)
+
         def layer_pass():
             # a decoder layer as deployed: q/k/v and gate/up concatenated, one rotate+quant per
             # distinct input (four per layer), four GEMVs
@@ -664,12 +690,14 @@ def bench_decode(b):
 
         bytes_layer = sum(K * N / 2 + 2 * N + T * K + 2 * T * N for (K, N) in wd.projections.values())
         res = {}
-        legs = [("quant+gemv", one_pass), ("layer_4quant_4gemv", layer_pass)]
+        legs = [("quant+gemv", one_pass), ("layer_4quant_4gemv", layer_pass),
+                ("layer_4quant_4grouped_gemv", layer_grouped_pass)]
         if T <= 4:
             legs.append(("quant+gemv_one_launch", fused_linear_pass))
             legs.append(("layer_4_one_launch_linears", layer_one_launch_pass))
         for name, fn in legs + [("gemv_only", gemv_only_pass),
                                 ("gemv_only_fused_qkv_gateup", gemv_fused_pass),
+                                ("gemv_only_grouped_4_launches", gemv_grouped_pass),
                                 ("gemv_only_4streams", gemv_streams_pass)]:
             run = b.graph_of(fn)
             ms = [m / len(layers) for m in b.time_blocks(run, args.decode_iters)]

@@ -293,6 +293,33 @@ int mquant_w4a8_gemm_rms(const int8_t *xq_dev, const uint8_t *w_prepacked_dev,
                          const float *split_scale_host, int32_t n_split,
                          void *workspace_dev, int64_t workspace_bytes, mquant_stream_t stream);
 
+/* One linear of a grouped decode launch: its prepacked weight (mquant_w4_prepack for
+ * (N, K)), per-channel scales fp16 [N], and output fp16 [T, N] with leading dimension ldy. */
+typedef struct {
+    const uint8_t *w_prepacked_dev;
+    const void *w_scale_dev;
+    void *y_dev;
+    int64_t ldy;
+    int32_t N;
+} mquant_linear_t;
+
+/*
+ * DEVICE.  The decode GEMV (Sec. 4, "custom W4A8 GEMV kernel"; the decode rows of the
+ * speed tables) for several linears that share their input -- q/k/v, gate/up of a
+ * decoder layer -- in ONE launch: for every linear l and row i < T
+ *     y_l[i, n] = fp16( (float(sum_k xq[i, k] * wq_l[n, k]) * s_i) * float(w_scale_l[n]) ),
+ * exactly what mquant_w4a8_gemm computes for each of them.  At decode a launch streams
+ * for a few microseconds, so its fixed cost matters: one launch instead of two or three.
+ *   xq_dev   : int8 [T, K] contiguous, 16-byte aligned; T <= 32 (ERR_UNSUPPORTED beyond)
+ *   lin_host : HOST array of n_linear (<= 4, ERR_UNSUPPORTED beyond) descriptors; the
+ *              outputs must not overlap
+ * Errors: as mquant_w4a8_gemm.  T == 0 or n_linear == 0 is a no-op; a linear with
+ * N == 0 is skipped.
+ */
+int mquant_w4a8_gemv_grouped(const int8_t *xq_dev, int32_t T, int32_t K, int32_t n_vis,
+                             float s_vis, float s_txt, const mquant_linear_t *lin_host,
+                             int32_t n_linear, mquant_stream_t stream);
+
 /* Workspace of the fused prefill entry: the int8 activations plus whatever
  * mquant_w4a8_gemm needs. */
 int64_t mquant_w4a8_linear_prefill_workspace_bytes(int32_t T, int32_t N, int32_t K);
@@ -444,7 +471,10 @@ int mquant_w4g128_gemm(const void *x_dev, int64_t ldx, const uint8_t *w_prepacke
 typedef enum {
     MQUANT_TUNE_GEMM_TILE = 0,      /* -1 = cost model; 0 = 256x256, 1 = 128x256, 2 = 192x128 */
     MQUANT_TUNE_GEMM_NOSPLIT = 1,   /* 0 = cost model; 1 = never split K */
-    MQUANT_TUNE_G128_TILE = 2       /* -1 = cost model; 0 = 128x256, 1 = 96x256 (weight-only GEMM) */
+    MQUANT_TUNE_G128_TILE = 2,      /* -1 = cost model; 0 = 128x256, 1 = 96x256 (weight-only GEMM) */
+    MQUANT_TUNE_GEMV_VARIANT = 3    /* -1 = default; 0..3 = waves per work-group x loads in flight per
+                                       wave of the decode GEMV: 4x8|4x4, 8x4|8x4, 8x8|4x8, 4x16|8x8
+                                       (16-channel units | 32-channel units) */
 } mquant_tune_key_t;
 
 /*

@@ -31,7 +31,7 @@ EXPORTS = (
     "mquant_rope_apply", "mquant_aifs_attention_workspace_bytes", "mquant_aifs_attention",
     "mquant_hadamard_quant_act_bits", "mquant_static_scale_from_absmax", "mquant_tune_set",
     "mquant_build_id",
-    "mquant_w4a8_linear_decode", "mquant_w4a8_linear_prefill_static",
+    "mquant_w4a8_linear_decode", "mquant_w4a8_linear_prefill_static", "mquant_w4a8_gemv_grouped",
     "mquant_w4g128_prepacked_bytes", "mquant_w4g128_prepack", "mquant_w4g128_gemm",
 )
 
@@ -46,6 +46,11 @@ class MQuantError(RuntimeError):
 
 class Span(ctypes.Structure):
     _fields_ = [("start", ctypes.c_int32), ("len", ctypes.c_int32)]
+
+
+class Linear(ctypes.Structure):
+    _fields_ = [("w_prepacked_dev", ctypes.c_void_p), ("w_scale_dev", ctypes.c_void_p),
+                ("y_dev", ctypes.c_void_p), ("ldy", ctypes.c_int64), ("N", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -84,6 +89,7 @@ def _load() -> ctypes.CDLL:
                                                i32, p, i64, p]
     lib.mquant_w4a8_linear_prefill_static.argtypes = [p, i64, p, p, p, p, i64, i32, i32, i32, i32, f32, f32,
                                                       i32, p]
+    lib.mquant_w4a8_gemv_grouped.argtypes = [p, i32, i32, i32, f32, f32, p, i32, p]
     lib.mquant_rope_apply.argtypes = [p, i64, p, i32, i32, i32, ctypes.c_double, p]
     lib.mquant_aifs_attention_workspace_bytes.restype = i64
     lib.mquant_aifs_attention_workspace_bytes.argtypes = [i32, i32, i32]
@@ -117,7 +123,7 @@ def build_id() -> str:
     return lib.mquant_build_id().decode()
 
 
-TUNE_GEMM_TILE, TUNE_GEMM_NOSPLIT, TUNE_G128_TILE = 0, 1, 2
+TUNE_GEMM_TILE, TUNE_GEMM_NOSPLIT, TUNE_G128_TILE, TUNE_GEMV_VARIANT = 0, 1, 2, 3
 
 
 def tune_set(key: int, value: int) -> None:
@@ -353,6 +359,22 @@ def w4a8_linear_prefill(x, perm_dev, w_prepacked, w_scale, N: int, n_vis: int, s
                                           s_vis, s_txt, had_block, _dp(workspace), ws_bytes,
                                           _stream()), "mquant_w4a8_linear_prefill")
     return out
+
+
+def w4a8_gemv_grouped(xq, linears, n_vis: int, s_vis: float, s_txt: float):
+    """linears: sequence of (w_prepacked, w_scale, N, out) sharing the input xq [T, K];
+    one launch computes every out [T, N]."""
+    T, K = xq.shape
+    _dense(xq, "xq")
+    arr = (Linear * max(len(linears), 1))()
+    for i, (wp, ws, N, out) in enumerate(linears):
+        _rows(out, "y"), _dense(ws, "w_scale")
+        arr[i].w_prepacked_dev, arr[i].w_scale_dev, arr[i].y_dev = _dp(wp), _dp(ws), _dp(out)
+        arr[i].ldy, arr[i].N = out.stride(0), N
+    _check(lib.mquant_w4a8_gemv_grouped(_dp(xq), T, K, n_vis, s_vis, s_txt,
+                                        ctypes.cast(arr, ctypes.c_void_p), len(linears), _stream()),
+           "mquant_w4a8_gemv_grouped")
+    return [l[3] for l in linears]
 
 
 STATIC_SCRATCH_BYTES = 128 << 20

@@ -35,6 +35,10 @@ extern "C" int mquant_tune_set(int32_t key, int32_t value)
         if (value < -1 || value > 1) return MQUANT_ERR_BAD_SHAPE;
         t.g128_tile.store(value, std::memory_order_relaxed);
         return MQUANT_OK;
+    case MQUANT_TUNE_GEMV_VARIANT:
+        if (value < -1 || value > 3) return MQUANT_ERR_BAD_SHAPE;
+        t.gemv_variant.store(value, std::memory_order_relaxed);
+        return MQUANT_OK;
     default: return MQUANT_ERR_BAD_SHAPE;
     }
 }

@@ -43,6 +43,7 @@ struct TuneState {
     std::atomic<int32_t> gemm_tile{-1};
     std::atomic<int32_t> gemm_nosplit{0};
     std::atomic<int32_t> g128_tile{-1};
+    std::atomic<int32_t> gemv_variant{-1};
 };
 TuneState &tune_state();
 

@@ -29,11 +29,9 @@
 
 #include "hadamard_segment.h"
 #include "mquant_internal.h"
+#include "w4a8_common.h"
 
 using namespace mquant;
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 
 namespace {
 
@@ -67,107 +65,6 @@ __global__ __launch_bounds__(256) void prepack_kernel(
         }
         out[o] = v;
     }
-}
-
-// ------------------------------------------------------------- shared pieces
-
-// 16 bytes of prepacked weights -> B operands of two MFMAs (values x16).
-__device__ __forceinline__ void unpack_w4x16(const uint4 p, v4i &b0, v4i &b1)
-{
-    b0[0] = static_cast<int>((p.x << 4) & 0xF0F0F0F0u);
-    b0[1] = static_cast<int>(p.x & 0xF0F0F0F0u);
-    b0[2] = static_cast<int>((p.y << 4) & 0xF0F0F0F0u);
-    b0[3] = static_cast<int>(p.y & 0xF0F0F0F0u);
-    b1[0] = static_cast<int>((p.z << 4) & 0xF0F0F0F0u);
-    b1[1] = static_cast<int>(p.z & 0xF0F0F0F0u);
-    b1[2] = static_cast<int>((p.w << 4) & 0xF0F0F0F0u);
-    b1[3] = static_cast<int>(p.w & 0xF0F0F0F0u);
-}
-
-__device__ __forceinline__ v4i as_v4i(const uint4 u)
-{
-    v4i r;
-    r[0] = static_cast<int>(u.x);
-    r[1] = static_cast<int>(u.y);
-    r[2] = static_cast<int>(u.z);
-    r[3] = static_cast<int>(u.w);
-    return r;
-}
-
-// Row of the 32x32 MFMA result held in accumulator register r by k-group g.
-__device__ __forceinline__ int acc_row(int r, int g) { return (r >> 2) * 8 + g * 4 + (r & 3); }
-
-// fp16 round-to-nearest-even of an fp32 value that has ALREADY been rounded to fp32.  The
-// empty asm keeps the compiler from merging the last fp32 multiply of the dequantisation
-// with the conversion into one v_fma_mixlo_f16, which rounds the exact product once, straight
-// to fp16: the defined result is the fp32 product rounded again (about 6 outputs in 10^5
-// differ by one fp16 ulp otherwise).
-__device__ __forceinline__ __half half_of_rounded_f32(float v)
-{
-    asm("" : "+v"(v));
-    return __float2half_rn(v);
-}
-
-// Everything the dequantising epilogue needs besides the accumulator and the
-// per-channel weight scale.  Activation scale of a row: the two static modality
-// scales split at row n_vis (Eq. (3)), or, for the per-token dynamic baseline,
-// one scale per row.  Rotation Magnitude Suppression (Sec. 3.2): n_split flagged
-// input channels were zeroed in the main weight; each lives on as an int4 row
-// split_w[j][0..N) (one byte per value) with one scale, and its product with the
-// token's int8 code of that channel is added to the main path before the store.
-constexpr int kEpiStatic = 0, kEpiRowScale = 1, kEpiSplit = 2;
-constexpr int kMaxSplitChannels = 64;     // flagged channels per linear
-
-struct Epilogue {
-    int32_t n_vis;
-    float s_vis, s_txt;
-    const float *rows;          // nullptr: static scales
-    int32_t n_split;            // 0: no split path
-    int32_t K;
-    const int8_t *xq;
-    const int8_t *split_w;
-    // Per-layer constants, passed by value so that a kernel reads them as scalars
-    // instead of chasing two more pointers per output.
-    int32_t split_idx[kMaxSplitChannels];
-    float split_scale[kMaxSplitChannels];
-
-    // EPI selects the code compiled into a kernel: the static path must not pay for
-    // the pointer test and the split loop (measured: 10 % of the 1280 x 3584 x 37888 GEMM).
-    template <int EPI>
-    __device__ __forceinline__ float scale_of(int32_t row) const
-    {
-        if constexpr (EPI == kEpiRowScale) return rows[row];
-        else return row < n_vis ? s_vis : s_txt;
-    }
-    // (float(acc) * s_row) * ws, plus the split terms in the order j = 0, 1, ...;
-    // one rounding per operation.  row < T and n < N.
-    template <int EPI>
-    __device__ __forceinline__ float dequant(int32_t acc, float s_row, int32_t row, int32_t n,
-                                             int32_t N, float ws) const
-    {
-        float v = (static_cast<float>(acc) * s_row) * ws;
-        if constexpr (EPI == kEpiSplit) {
-            for (int32_t j = 0; j < n_split; ++j) {
-                const int32_t c = split_idx[j];           // validated on the host
-                const int32_t p = static_cast<int32_t>(xq[static_cast<int64_t>(row) * K + c]) *
-                                  static_cast<int32_t>(split_w[static_cast<int64_t>(j) * N + n]);
-                v = v + (static_cast<float>(p) * s_row) * split_scale[j];
-            }
-        }
-        return v;
-    }
-};
-
-template <int EPI>
-__device__ __forceinline__ void store_out(int32_t acc16, int32_t row, int32_t n, const Epilogue &ep,
-                                          float ws, __half *y, int64_t ldy, int32_t *acc_out,
-                                          int32_t N)
-{
-    const int32_t acc = acc16 >> 4;                       // exact: acc16 = 16 * acc
-    const float s_row = ep.scale_of<EPI>(row);
-    y[static_cast<int64_t>(row) * ldy + n] =
-        half_of_rounded_f32(ep.dequant<EPI>(acc, s_row, row, n, N, ws));
-    if (acc_out) acc_out[static_cast<int64_t>(row) * N + n] = acc;
 }
 
 // ------------------------------------------------------------------- GEMM
@@ -1013,6 +910,17 @@ int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void
                   int32_t *acc_out, int32_t T, int32_t N, int32_t K, Epilogue ep, void *workspace,
                   int64_t workspace_bytes, hipStream_t stream)
 {
+    if (gemv_stream_takes(T, K)) {
+        GemvGroup grp = {};
+        grp.n = 1;
+        grp.p[0].wp = reinterpret_cast<const uint4 *>(wp);
+        grp.p[0].w_scale = static_cast<const __half *>(w_scale);
+        grp.p[0].y = static_cast<__half *>(y);
+        grp.p[0].acc_out = acc_out;
+        grp.p[0].ldy = ldy;
+        grp.p[0].N = N;
+        return gemv_stream_dispatch<EPI>(xq, T, K, grp, ep, stream);
+    }
     if (T <= kGemvMaxT || K % 128 != 0) {
         // GEMV handles 32 rows per pass; walk taller inputs in slabs of 32 rows
         // (only reached for K % 128 != 0, which the prefill kernel does not take).

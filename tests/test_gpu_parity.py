@@ -364,6 +364,63 @@ def test_gemv_small_shapes_full(mq, T):
     check_y(y.cpu().numpy(), ref, f"gemv T={T}")
 
 
+@pytest.mark.parametrize("T", [1, 3, 4, 7])
+@pytest.mark.parametrize("K,Ns", [(3584, (3584, 512, 512)), (1024, (18944, 18944)), (18944, (3584,)),
+                                  (384, (40, 0, 200, 72))])
+def test_gemv_grouped_equals_the_oracle_per_linear(mq, T, K, Ns):
+    """Several linears sharing one input in one launch (q/k/v; gate/up): every output of every
+    linear against the oracle, bit for bit on the fp16 value (accumulators are checked through
+    the single-linear entry on the same kernel); untouched padding columns stay untouched."""
+    say(f"grouped gemv T={T} K={K} Ns={Ns}")
+    rng = np.random.default_rng(T * 1000 + K + len(Ns))
+    xq = rng.integers(-128, 128, size=(T, K), dtype=np.int8)
+    V, s_vis, s_txt = min(T, 2), 0.21, 0.034
+    lin, want = [], []
+    for N in Ns:
+        packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+        w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+        out = torch.full((T, N + 8), 3.0, dtype=torch.float16, device="cuda")
+        wp = mq.w4_prepack(dev(packed)) if N else torch.empty(0, dtype=torch.uint8, device="cuda")
+        lin.append((wp, dev(w_scale), N, out[:, :N]))
+        acc = orc.gemm_i8_i4_i32(xq, orc.unpack_w4(packed)) if N else np.zeros((T, 0), dtype=np.int32)
+        want.append(orc.dequant(acc, V, s_vis, s_txt, w_scale)[1] if N else np.zeros((T, 0), dtype=np.float16))
+    xqd = dev(xq)
+    mq.w4a8_gemv_grouped(xqd, lin, V, s_vis, s_txt)
+    torch.cuda.synchronize()
+    for (wp, ws, N, out), w in zip(lin, want):
+        got = out.cpu().numpy()
+        assert (got.view(np.uint16) == w.view(np.uint16)).all(), f"N={N}"
+        if N:
+            assert torch.equal(mq.w4a8_gemm(xqd, wp, ws, N, V, s_vis, s_txt), out)
+    # the padding columns of every output buffer still hold the fill value
+    for (wp, ws, N, out) in lin:
+        buf = out._base if out._base is not None else out
+        assert bool((buf[:, N:] == 3.0).all())
+
+
+def test_gemv_grouped_argument_errors(mq):
+    P = 0x1000
+    L = mq.lib
+    lin = (mq.Linear * 5)()
+    for i in range(5):
+        lin[i].w_prepacked_dev, lin[i].w_scale_dev, lin[i].y_dev, lin[i].ldy, lin[i].N = P, P, P, 64, 64
+    lp = __import__("ctypes").cast(lin, __import__("ctypes").c_void_p)
+    f = L.mquant_w4a8_gemv_grouped
+    assert f(P, 1, 128, 0, 1.0, 1.0, lp, 5, None) == mq.ERR_UNSUPPORTED          # more than four linears
+    assert f(P, 33, 128, 0, 1.0, 1.0, lp, 2, None) == mq.ERR_UNSUPPORTED         # not a decode shape
+    assert f(P, 1, 100, 0, 1.0, 1.0, lp, 2, None) == mq.ERR_UNSUPPORTED          # K % 64
+    assert f(None, 1, 128, 0, 1.0, 1.0, lp, 2, None) == mq.ERR_NULL
+    assert f(P, 1, 128, 0, 1.0, 1.0, None, 2, None) == mq.ERR_NULL
+    assert f(P, 1, 128, 2, 1.0, 1.0, lp, 2, None) == mq.ERR_BAD_SHAPE            # n_vis > T
+    assert f(P, 1, 128, 0, 0.0, 1.0, lp, 2, None) == mq.ERR_BAD_SHAPE
+    lin[1].ldy = 32
+    assert f(P, 1, 128, 0, 1.0, 1.0, lp, 2, None) == mq.ERR_BAD_SHAPE            # ldy < N
+    lin[1].ldy, lin[1].y_dev = 64, None
+    assert f(P, 1, 128, 0, 1.0, 1.0, lp, 2, None) == mq.ERR_NULL
+    assert f(P, 0, 128, 0, 1.0, 1.0, lp, 2, None) == mq.OK                       # T == 0
+    assert f(P, 1, 128, 0, 1.0, 1.0, lp, 0, None) == mq.OK
+
+
 def test_empty_inputs_are_noops(mq):
     say("empty inputs")
     e16 = torch.empty((0, 512), dtype=torch.float16, device="cuda")
