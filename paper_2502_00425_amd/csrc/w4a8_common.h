@@ -116,7 +116,8 @@ __device__ __forceinline__ void store_out(int32_t acc16, int32_t row, int32_t n,
 
 // ---- the streaming GEMV of w4a8_gemv.hip (T <= kGemvStreamMaxT rows), also reached through
 // the single-linear entry points
-constexpr int kGemvStreamMaxT = 4;
+constexpr int kGemvStreamMaxT = 16;         // rows the streaming kernels take
+constexpr int kGemvStreamLdsMaxT = 4;       // ... of which the form with xq resident in LDS
 constexpr int kGemvMaxGroup = 4;            // linears per grouped launch
 
 struct GemvProblem {
@@ -135,7 +136,7 @@ struct GemvGroup {
 };
 
 // True when the streaming kernel handles this shape (else the callers use the tile kernel).
-bool gemv_stream_takes(int32_t T, int32_t K);
+bool gemv_stream_takes(int32_t T, int32_t K, int64_t n_tiles);
 
 template <int EPI>
 int gemv_stream_dispatch(const int8_t *xq, int32_t T, int32_t K, GemvGroup grp, const Epilogue &ep,

@@ -910,7 +910,7 @@ int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void
                   int32_t *acc_out, int32_t T, int32_t N, int32_t K, Epilogue ep, void *workspace,
                   int64_t workspace_bytes, hipStream_t stream)
 {
-    if (gemv_stream_takes(T, K)) {
+    if (gemv_stream_takes(T, K, ceil_div(N, kPackN))) {
         GemvGroup grp = {};
         grp.n = 1;
         grp.p[0].wp = reinterpret_cast<const uint4 *>(wp);

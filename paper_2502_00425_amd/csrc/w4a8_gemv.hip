@@ -192,6 +192,170 @@ __global__ __launch_bounds__(WAVES * 64) void w4a8_gemv_stream_kernel(
     }
 }
 
+// The same stream for up to 16 rows (and for few rows of a very long K): the T rows of xq no
+// longer fit LDS as a whole, so they are streamed too.  With every weight load a wave requests
+// the 64 F input channels of all rows that go with it (16 rows x 64 F bytes: one or two 16-byte
+// loads per lane, 4 lanes per row, fully coalesced), and passes them through a wave-private LDS
+// slot on their way into the matrix instruction's token operand (lane = token there).  Two
+// slots alternate: the rows of step s + 1 are written while step s is computed.  No barrier is
+// involved: a wave's LDS operations complete in order.
+template <int F, int WAVES, int DEPTH, int EPI>
+__global__ __launch_bounds__(WAVES * 64) void w4a8_gemv_stream_x_kernel(
+    const int8_t *__restrict__ xq, int32_t T, int32_t K, GemvGroup grp, Epilogue ep)
+{
+    static_assert(F == 1 || F == 2, "channels per work-group: 32 or 16");
+    constexpr int CH = 32 / F;
+    constexpr int STEP = 64 * F;                  // input channels per wave-load
+    constexpr int PITCH = STEP + 16;              // row pitch of a slot: conflict-free fragment reads
+    constexpr int SLOT = 16 * PITCH;
+    constexpr int kSlots = WAVES * 2 * SLOT, kRed = WAVES * 16 * CH * 4;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[kSlots > kRed ? kSlots : kRed];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+
+    int32_t pi = 0, unit = blockIdx.x;
+    while (pi + 1 < grp.n && unit >= grp.p[pi].units) {
+        unit -= grp.p[pi].units;
+        ++pi;
+    }
+    const GemvProblem &pr = grp.p[pi];
+    const int32_t N = pr.N;
+    const int32_t k_tiles = K / kPackK;
+    const int32_t loads = k_tiles / F;
+    const int32_t per_wave = (loads + WAVES - 1) / WAVES;
+    const int32_t j0 = wave * per_wave;
+    int32_t j1 = j0 + per_wave;
+    j1 = j1 < loads ? j1 : loads;
+    const int32_t n_mine = j1 > j0 ? j1 - j0 : 0;
+
+    const int32_t nt = unit / F, h = unit % F;
+    int32_t lane_vec, k_lane;
+    if constexpr (F == 1) {
+        lane_vec = lane;
+        k_lane = (lane >> 5) * 32;
+    } else {
+        const int q = lane >> 4, c = lane & 15;
+        lane_vec = (q >> 1) * 64 + (q & 1) * 32 + h * 16 + c;
+        k_lane = q * 32;
+    }
+    const uint4 *wsrc = pr.wp + static_cast<int64_t>(nt) * k_tiles * 64 + lane_vec;
+    // past the wave's range both loads stay (branch-free pipeline) and read the start of xq
+    auto load_w = [&](int32_t j) -> uint4 {
+        const uint4 *src = j < j1 ? wsrc + static_cast<int64_t>(j) * (64 * F)
+                                  : reinterpret_cast<const uint4 *>(xq);
+        const v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src));
+        return make_uint4(t[0], t[1], t[2], t[3]);
+    };
+    // x of a step: lane -> row lane / 4 (clamped to a valid row), piece lane % 4 of 16 F bytes
+    const int xr = lane >> 2, xp = lane & 3;
+    const int8_t *xsrc = xq + static_cast<int64_t>(xr < T ? xr : T - 1) * K + xp * (16 * F);
+    auto load_x = [&](int32_t j, v4u (&dst)[F]) {
+        const int8_t *src = j < j1 ? xsrc + static_cast<int64_t>(j) * STEP : xq;
+#pragma unroll
+        for (int v = 0; v < F; ++v) dst[v] = *reinterpret_cast<const v4u *>(src + v * 16);
+    };
+
+    v4u xa[DEPTH][F];
+    uint4 b[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+        load_x(j0 + d, xa[d]);
+        b[d] = load_w(j0 + d);
+    }
+    const int32_t n_ch = nt * 32 + h * CH + (lane & (CH - 1));
+    const __half ws_h = pr.w_scale[n_ch < N ? n_ch : N - 1];
+    __builtin_amdgcn_sched_barrier(0);
+
+    uint8_t *slots = smem + wave * (2 * SLOT);
+    auto stage_x = [&](int slot, const v4u (&src)[F]) {
+#pragma unroll
+        for (int v = 0; v < F; ++v)
+            *reinterpret_cast<v4u *>(slots + slot * SLOT + xr * PITCH + xp * (16 * F) + v * 16) = src[v];
+    };
+    const int m = F == 1 ? (lane & 31) : (lane & 15);           // token of this lane in the instruction
+    const uint8_t *afrag = slots + (m & 15) * PITCH + k_lane;    // rows 16..31 of the 32-row form repeat
+    auto read_a = [&](int slot, uint4 &a0, uint4 &a1) {
+        a0 = *reinterpret_cast<const uint4 *>(afrag + slot * SLOT);
+        a1 = *reinterpret_cast<const uint4 *>(afrag + slot * SLOT + 16);
+    };
+
+    typedef typename std::conditional<F == 1, v16i, v4i>::type acc_t;
+    acc_t acc0, acc1;
+#pragma unroll
+    for (int r = 0; r < (F == 1 ? 16 : 4); ++r) {
+        acc0[r] = 0;
+        acc1[r] = 0;
+    }
+
+    stage_x(0, xa[0]);
+    for (int32_t i = 0; i < n_mine; i += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const int32_t j = j0 + i + d;
+            // DEPTH is even, so the slot of a step is the parity of d
+            stage_x((d + 1) & 1, xa[(d + 1) % DEPTH]);            // rows of the next step
+            uint4 a0, a1;
+            read_a(d & 1, a0, a1);
+            const uint32_t msk = j < j1 ? 0xFFFFFFFFu : 0u;       // wave-uniform
+            uint4 bb = b[d];
+            bb.x &= msk;
+            bb.y &= msk;
+            bb.z &= msk;
+            bb.w &= msk;
+            // refill this step's register sets: x before w, the order in which they are needed
+            load_x(j + DEPTH, xa[d]);
+            b[d] = load_w(j + DEPTH);
+            v4i b0, b1;
+            unpack_w4x16(bb, b0, b1);
+            if constexpr (F == 1) {
+                acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a0), b0, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a1), b1, acc1, 0, 0, 0);
+            } else {
+                acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(as_v4i(a0), b0, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(as_v4i(a1), b1, acc1, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    __syncthreads();                                   // the sums reuse the slots
+
+    // rows 0..15 of the result: 32x32x32 keeps row (r / 4) * 8 + 4 g + r % 4 in register r < 8 of
+    // k-group g; 16x16x64 keeps row 4 q + r in register r of lane group q
+    int32_t (*red)[16][CH] = reinterpret_cast<int32_t (*)[16][CH]>(smem);      // [WAVES][16][CH]
+    if constexpr (F == 1) {
+        const int g = lane >> 5;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) red[wave][acc_row(r, g)][lane & 31] = acc0[r] + acc1[r];
+    } else {
+        const int q = lane >> 4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[wave][4 * q + r][lane & 15] = acc0[r] + acc1[r];
+    }
+    __syncthreads();
+    const float wsf = __half2float(ws_h);              // this thread's channel below is lane % CH
+    for (int32_t idx = threadIdx.x; idx < T * CH; idx += WAVES * 64) {
+        const int32_t row = idx / CH, c = idx % CH;
+        const int32_t n = nt * 32 + h * CH + c;
+        if (n < N) {
+            int32_t sum = 0;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) sum += red[w][row][c];
+            store_out<EPI>(sum, row, n, ep, wsf, pr.y, pr.ldy, pr.acc_out, N);
+        }
+    }
+}
+
+template <int F, int WAVES, int DEPTH, int EPI>
+int launch_stream_x(const int8_t *xq, int32_t T, int32_t K, const GemvGroup &grp, const Epilogue &ep,
+                    int32_t total_units, hipStream_t stream)
+{
+    static_assert(DEPTH % 2 == 0, "slot parity");
+    MQ_LAUNCH((w4a8_gemv_stream_x_kernel<F, WAVES, DEPTH, EPI>), dim3(static_cast<unsigned>(total_units)),
+              dim3(WAVES * 64), 0, stream, xq, T, K, grp, ep);
+    return launch_status();
+}
+
 // The T rows of xq pass through registers on their way to LDS: at most NX 16-byte pieces per
 // thread, i.e. T * K <= kStreamMaxXq bytes whatever the work-group size.
 constexpr int kStreamMaxXq = 80 * 1024;
@@ -232,10 +396,20 @@ int launch_stream_nx(const int8_t *xq, int32_t T, int32_t K, const GemvGroup &gr
 
 namespace mquant {
 
-bool gemv_stream_takes(int32_t T, int32_t K)
+// Which shapes the two streaming kernels take (measured against the tile kernel they replace,
+// 28 distinct 7B layers, one HIP graph per pass):
+//   - up to 4 rows whose T * K bytes fit the LDS copy: every shape (T = 1: 3584 -> 18944 in 8.2 us
+//     against 8.9, 18944 -> 3584 in 8.1 against 10.2, 3584 -> 3584 in 3.9 against 4.0);
+//   - 5 to 16 rows: matrices with at most 128 output tiles, where 16-channel units double the
+//     work-groups (T = 16: 18944 -> 3584 in 11.9 us against 15.5, 3584 -> 3584 in 4.4 against 5.1).
+//     With many output tiles the tile kernel, which stages four k-tiles of activations per LDS
+//     round trip, stays ahead (3584 -> 18944: 10.9 us against 12.1), and so it does for few rows
+//     of a K too long for the LDS copy.
+bool gemv_stream_takes(int32_t T, int32_t K, int64_t n_tiles)
 {
-    return T >= 1 && T <= kGemvStreamMaxT && K % 128 == 0 &&
-           static_cast<int64_t>(T) * K <= kStreamMaxXq;
+    if (T < 1 || K % 128 != 0) return false;
+    if (T <= kGemvStreamLdsMaxT) return static_cast<int64_t>(T) * K <= kStreamMaxXq;
+    return T <= kGemvStreamMaxT && n_tiles <= kNumCU / 2;
 }
 
 // Shared by the single-linear entry points (a group of one) and the grouped entry.
@@ -257,6 +431,12 @@ int gemv_stream_dispatch(const int8_t *xq, int32_t T, int32_t K, GemvGroup grp, 
     }
     if (total <= 0 || total > 0x7fffffff) return MQUANT_ERR_BAD_SHAPE;
     const int32_t units = static_cast<int32_t>(total);
+    if (T > kGemvStreamLdsMaxT) {
+        // more rows than the LDS copy of xq is compiled for: xq streamed next to the weights
+        // (only few-tile matrices come here, see gemv_stream_takes)
+        if (halves) return launch_stream_x<2, 8, 4, EPI>(xq, T, K, grp, ep, units, stream);
+        return launch_stream_x<1, 4, 4, EPI>(xq, T, K, grp, ep, units, stream);
+    }
     if constexpr (EPI == kEpiStatic) {
         // shapes of the work-group for tuning runs (mquant_tune_set); the default is variant 0
         const int32_t variant = tune_state().gemv_variant.load(std::memory_order_relaxed);
@@ -319,7 +499,9 @@ extern "C" int mquant_w4a8_gemv_grouped(const int8_t *xq, int32_t T, int32_t K, 
     if (grp.n == 0) return MQUANT_OK;
     Epilogue ep = {};
     ep.n_vis = n_vis, ep.s_vis = s_vis, ep.s_txt = s_txt, ep.K = K, ep.xq = xq;
-    if (!gemv_stream_takes(T, K)) {
+    int64_t group_tiles = 0;
+    for (int32_t i = 0; i < grp.n; ++i) group_tiles += ceil_div(grp.p[i].N, kPackN);
+    if (!gemv_stream_takes(T, K, group_tiles)) {
         // outside the streaming kernel's range: one plain call per linear
         for (int32_t i = 0; i < grp.n; ++i) {
             const int st = mquant_w4a8_gemm(xq, reinterpret_cast<const uint8_t *>(grp.p[i].wp), grp.p[i].w_scale,

@@ -398,6 +398,31 @@ def test_gemv_grouped_equals_the_oracle_per_linear(mq, T, K, Ns):
         assert bool((buf[:, N:] == 3.0).all())
 
 
+@pytest.mark.parametrize("T,N,K", [(5, 200, 1024), (8, 72, 128), (11, 3584, 3584), (16, 520, 18944), (13, 16416, 256),
+                                   (16, 18944, 384), (4, 264, 29568), (9, 40, 640)])
+def test_gemv_streamed_rows_full(mq, T, N, K):
+    """5..16 rows (and few rows of a very long K): the GEMV that streams xq next to the weights,
+    16-channel units (few output tiles) and 32-channel units (N >= 16384); accumulators and fp16
+    outputs of every element against the oracle."""
+    say(f"gemv streamed rows T={T} N={N} K={K}")
+    rng = np.random.default_rng(T * 31 + N + K)
+    xq = rng.integers(-128, 128, size=(T, K), dtype=np.int8)
+    packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+    V, s_vis, s_txt = T // 2, 0.2, 0.03
+    acc_want = orc.gemm_i8_i4_i32(xq, orc.unpack_w4(packed))
+    ref, y_want = orc.dequant(acc_want, V, s_vis, s_txt, w_scale)
+    wp = mq.w4_prepack(dev(packed))
+    acc = torch.full((T, N), -7, dtype=torch.int32, device="cuda")
+    ybuf = torch.full((T, N + 8), 9.0, dtype=torch.float16, device="cuda")
+    mq.w4a8_gemm(dev(xq), wp, dev(w_scale), N, V, s_vis, s_txt, out=ybuf[:, :N], acc_out=acc)
+    assert (acc.cpu().numpy() == acc_want).all()
+    yb = ybuf.cpu().numpy()
+    assert (yb[:, :N].view(np.uint16) == y_want.view(np.uint16)).all()
+    check_y(yb[:, :N], ref, "gemv streamed rows")
+    assert (yb[:, N:] == 9.0).all()
+
+
 def test_gemv_grouped_argument_errors(mq):
     P = 0x1000
     L = mq.lib
