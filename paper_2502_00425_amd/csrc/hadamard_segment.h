@@ -181,26 +181,30 @@ struct Segment {
     float v[C][8];
     bool valid[C];
 
-    __device__ __forceinline__ void load_rotate(const __half *row, int32_t sidx, int32_t K, int lane)
+    // The 16 bytes (8 fp16 channels) of chunk c of segment sidx that this lane owns; zeros past K.
+    static __device__ __forceinline__ uint4 load_chunk(const __half *row, int32_t sidx, int c, int32_t K,
+                                                       int lane, bool &in_range)
     {
+        const int32_t k0 = sidx * SEG + c * 512 + lane * 8;
+        in_range = k0 < K;
+        return in_range ? *reinterpret_cast<const uint4 *>(row + k0) : make_uint4(0u, 0u, 0u, 0u);
+    }
+
+    __device__ __forceinline__ void set_chunk(int c, const uint4 raw, bool in_range)
+    {
+        valid[c] = in_range;
+        const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
 #pragma unroll
-        for (int c = 0; c < C; ++c) {
-            const int32_t k0 = sidx * SEG + c * 512 + lane * 8;
-            valid[c] = k0 < K;
-            if (valid[c]) {
-                const uint4 raw = *reinterpret_cast<const uint4 *>(row + k0);
-                const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float2 f = __half22float2(h2[j]);
-                    v[c][2 * j] = f.x;
-                    v[c][2 * j + 1] = f.y;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) v[c][j] = 0.0f;
-            }
+        for (int j = 0; j < 4; ++j) {
+            const float2 f = __half22float2(h2[j]);
+            v[c][2 * j] = f.x;
+            v[c][2 * j + 1] = f.y;
         }
+    }
+
+    // All stages h = 1 ... B/2 on the chunks set before.
+    __device__ __forceinline__ void rotate(int lane)
+    {
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             register_stages<B>(v[c]);
@@ -221,6 +225,17 @@ struct Segment {
                 }
             }
         }
+    }
+
+    __device__ __forceinline__ void load_rotate(const __half *row, int32_t sidx, int32_t K, int lane)
+    {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            bool in_range;
+            const uint4 raw = load_chunk(row, sidx, c, K, lane, in_range);
+            set_chunk(c, raw, in_range);
+        }
+        rotate(lane);
     }
 
     __device__ __forceinline__ float absmax(float m) const

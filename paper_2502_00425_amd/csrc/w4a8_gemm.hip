@@ -1213,6 +1213,15 @@ extern "C" int mquant_w4a8_linear_decode(const void *x, int64_t ldx, const uint8
     const uint4 *wpp = reinterpret_cast<const uint4 *>(wp);
     const __half *wsc = static_cast<const __half *>(w_scale);
     __half *yh = static_cast<__half *>(y);
+    {
+        // the streaming kernel when the shape is in its range
+        GemvGroup grp = {};
+        grp.n = 1;
+        grp.p[0].wp = wpp, grp.p[0].w_scale = wsc, grp.p[0].y = yh, grp.p[0].acc_out = nullptr;
+        grp.p[0].ldy = ldy, grp.p[0].N = N;
+        const int st = gemv_stream_fused(xh, ldx, T, K, had_block, grp, ep, c_vis, c_txt, stream_h);
+        if (st != MQUANT_ERR_UNSUPPORTED) return st;
+    }
     switch (had_block) {
     case 1: return launch_decode_fused<1>(xh, ldx, wpp, wsc, yh, ldy, T, N, K, ep, c_vis, c_txt, stream_h);
     case 128: return launch_decode_fused<128>(xh, ldx, wpp, wsc, yh, ldy, T, N, K, ep, c_vis, c_txt, stream_h);

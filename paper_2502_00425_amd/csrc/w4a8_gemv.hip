@@ -19,6 +19,7 @@
 #include <hip/hip_fp16.h>
 #include <math.h>
 
+#include "hadamard_segment.h"
 #include "mquant_internal.h"
 #include "w4a8_common.h"
 
@@ -28,11 +29,22 @@ namespace {
 
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
-template <int F, int WAVES, int DEPTH, int NX, int EPI>
+// HB > 0: the rotate + quantize front end runs inside the kernel (Sec. 3.2 rotation with
+// Hadamard block HB, Eq. (2)/(3) static quantizer: the wave-level code of the stand-alone
+// kernel).  x is then the fp16 input [T, ldx]; every work-group rotates and quantizes the T
+// rows itself, one 512-channel segment per wave at a time (NX = segments per wave), straight
+// into the LDS copy that the xq path fills by copying.  The work is redundant across
+// work-groups but runs under the latency of the first weight loads, and it saves a launch per
+// linear, which at decode costs as much as a small GEMV.
+template <int F, int WAVES, int DEPTH, int NX, int EPI, int HB>
 __global__ __launch_bounds__(WAVES * 64) void w4a8_gemv_stream_kernel(
-    const int8_t *__restrict__ xq, int32_t T, int32_t K, GemvGroup grp, Epilogue ep)
+    const int8_t *__restrict__ xq, int32_t T, int32_t K, GemvGroup grp, Epilogue ep,
+    const __half *__restrict__ x, int64_t ldx, float c_vis, float c_txt)
 {
     static_assert(F == 1 || F == 2, "channels per work-group: 32 or 16");
+    static_assert(HB == 0 || HB <= 512, "one 512-channel segment per wave and step");
+    // 16 bytes that every wave has in cache, for loads past a wave's range
+    const uint4 *hot = HB > 0 ? reinterpret_cast<const uint4 *>(x) : reinterpret_cast<const uint4 *>(xq);
     constexpr int CH = 32 / F;                    // output channels of a work-group
     constexpr int STEP = 64 * F;                  // input channels one wave-load covers
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];   // T rows of xq, pitch K + 16
@@ -74,13 +86,47 @@ __global__ __launch_bounds__(WAVES * 64) void w4a8_gemv_stream_kernel(
     const uint4 *wsrc = pr.wp + static_cast<int64_t>(nt) * k_tiles * 64 + lane_vec;
     auto load_w = [&](int32_t j) -> uint4 {
         // Past the wave's range the load stays (the pipeline is branch-free) but reads the first
-        // 16 bytes of xq, which every wave has in cache; its value is masked below.
-        const uint4 *src = j < j1 ? wsrc + static_cast<int64_t>(j) * (64 * F)
-                                  : reinterpret_cast<const uint4 *>(xq);
+        // 16 bytes of the input, which every wave has in cache; its value is masked below.
+        const uint4 *src = j < j1 ? wsrc + static_cast<int64_t>(j) * (64 * F) : hot;
         const v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(src));
         return make_uint4(t[0], t[1], t[2], t[3]);
     };
+    uint4 b[DEPTH];
+    const int32_t n_ch = nt * 32 + h * CH + (lane & (CH - 1));            // this lane's output channel
+    __half ws_h;
 
+    if constexpr (HB > 0) {
+        // ---- fused front end: x segments first (they must arrive first), then the weights
+        using Seg = Segment<HB>;
+        const int32_t spr = (K + Seg::SEG - 1) / Seg::SEG;                  // segments per row
+        const int32_t total_seg = T * spr;                                  // <= NX * WAVES
+        uint4 raw[NX];
+        bool in_range[NX];
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            int32_t sg = wave + i * WAVES;
+            sg = sg < total_seg ? sg : total_seg - 1;
+            const int32_t r = (sg >= spr ? 1 : 0) + (sg >= 2 * spr ? 1 : 0) + (sg >= 3 * spr ? 1 : 0);
+            raw[i] = Seg::load_chunk(x + static_cast<int64_t>(r) * ldx, sg - r * spr, 0, K, lane, in_range[i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) b[d] = load_w(j0 + d);
+        ws_h = pr.w_scale[n_ch < N ? n_ch : N - 1];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            const int32_t sg = wave + i * WAVES;
+            if (sg < total_seg) {                                           // wave-uniform
+                const int32_t r = (sg >= spr ? 1 : 0) + (sg >= 2 * spr ? 1 : 0) + (sg >= 3 * spr ? 1 : 0);
+                Seg s;
+                s.set_chunk(0, raw[i], in_range[i]);
+                s.rotate(lane);
+                s.quant_store(r < ep.n_vis ? c_vis : c_txt, reinterpret_cast<int8_t *>(smem) + r * pitch,
+                              sg - r * spr, lane);
+            }
+        }
+    } else {
     // Loads return in the order they were issued, so the order of issue is the order of
     // arrival: first the T rows of xq (L2 hits; NX 16-byte pieces per thread, branch-free with
     // clamped addresses), then the first DEPTH weight loads (HBM).  The copy of xq into LDS
@@ -97,12 +143,9 @@ __global__ __launch_bounds__(WAVES * 64) void w4a8_gemv_stream_kernel(
         xr[i] = *reinterpret_cast<const v4u *>(xq + static_cast<int64_t>(v) * 16);
     }
     __builtin_amdgcn_sched_barrier(0);            // the scheduler must not move weight loads ahead of these
-    uint4 b[DEPTH];
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) b[d] = load_w(j0 + d);
-
-    const int32_t n_ch = nt * 32 + h * CH + (lane & (CH - 1));            // this lane's output channel
-    const __half ws_h = pr.w_scale[n_ch < N ? n_ch : N - 1];
+    ws_h = pr.w_scale[n_ch < N ? n_ch : N - 1];
     __builtin_amdgcn_sched_barrier(0);
 
     // Pieces past the end were clamped to the last one: they store the same bytes to the same
@@ -115,6 +158,7 @@ __global__ __launch_bounds__(WAVES * 64) void w4a8_gemv_stream_kernel(
         const int32_t r = (v >= vec_per_row ? 1 : 0) + (v >= 2 * vec_per_row ? 1 : 0) +
                           (v >= 3 * vec_per_row ? 1 : 0);
         *reinterpret_cast<v4u *>(smem + (v + r) * 16) = xr[i];            // row pitch K + 16
+    }
     }
     __syncthreads();
 
@@ -361,14 +405,15 @@ int launch_stream_x(const int8_t *xq, int32_t T, int32_t K, const GemvGroup &grp
 constexpr int kStreamMaxXq = 80 * 1024;
 constexpr int kStreamMaxLds = kStreamMaxXq + 16 * kGemvStreamMaxT;
 
-template <int F, int WAVES, int DEPTH, int NX, int EPI>
+template <int F, int WAVES, int DEPTH, int NX, int EPI, int HB = 0>
 int launch_stream(const int8_t *xq, int32_t T, int32_t K, const GemvGroup &grp, const Epilogue &ep,
-                  int32_t total_units, hipStream_t stream)
+                  int32_t total_units, hipStream_t stream, const __half *x = nullptr, int64_t ldx = 0,
+                  float c_vis = 0.0f, float c_txt = 0.0f)
 {
     size_t lds = static_cast<size_t>(T) * (K + 16);
     const size_t red = static_cast<size_t>(WAVES) * 4 * (32 / F) * 4;
     lds = lds > red ? lds : red;
-    auto kern = w4a8_gemv_stream_kernel<F, WAVES, DEPTH, NX, EPI>;
+    auto kern = w4a8_gemv_stream_kernel<F, WAVES, DEPTH, NX, EPI, HB>;
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -376,7 +421,8 @@ int launch_stream(const int8_t *xq, int32_t T, int32_t K, const GemvGroup &grp, 
             return MQUANT_ERR_HIP;
         attr_set.store(true, std::memory_order_release);
     }
-    MQ_LAUNCH(kern, dim3(static_cast<unsigned>(total_units)), dim3(WAVES * 64), lds, stream, xq, T, K, grp, ep);
+    MQ_LAUNCH(kern, dim3(static_cast<unsigned>(total_units)), dim3(WAVES * 64), lds, stream, xq, T, K, grp, ep,
+              x, ldx, c_vis, c_txt);
     return launch_status();
 }
 
@@ -455,6 +501,41 @@ int gemv_stream_dispatch(const int8_t *xq, int32_t T, int32_t K, GemvGroup grp, 
     }
     if (halves) return launch_stream_nx<2, 4, 8, EPI>(xq, T, K, grp, ep, units, stream);
     return launch_stream_nx<1, 4, 4, EPI>(xq, T, K, grp, ep, units, stream);
+}
+
+// The one-launch decode linear on the streaming kernel; ERR_UNSUPPORTED when the shape is
+// outside its range (the caller then uses the tile kernel's fused form).
+template <int HB>
+static int stream_fused_hb(const __half *x, int64_t ldx, int32_t T, int32_t K, GemvGroup grp, const Epilogue &ep,
+                           float c_vis, float c_txt, hipStream_t stream)
+{
+    constexpr int kSegSmall = 2, kSegLarge = 10;                 // segments per wave the kernel is compiled for
+    const int64_t tiles = ceil_div(grp.p[0].N, kPackN);
+    const bool halves = tiles < 2 * kNumCU;
+    grp.p[0].units = static_cast<int32_t>(tiles * (halves ? 2 : 1));
+    const int32_t units = grp.p[0].units;
+    const int64_t segs = static_cast<int64_t>(T) * ceil_div(K, 512);
+    if (segs > kSegLarge * 4) return MQUANT_ERR_UNSUPPORTED;
+    const bool small = segs <= kSegSmall * 4;
+    if (halves) {
+        if (small) return launch_stream<2, 4, 8, kSegSmall, kEpiStatic, HB>(nullptr, T, K, grp, ep, units, stream, x, ldx, c_vis, c_txt);
+        return launch_stream<2, 4, 8, kSegLarge, kEpiStatic, HB>(nullptr, T, K, grp, ep, units, stream, x, ldx, c_vis, c_txt);
+    }
+    if (small) return launch_stream<1, 4, 4, kSegSmall, kEpiStatic, HB>(nullptr, T, K, grp, ep, units, stream, x, ldx, c_vis, c_txt);
+    return launch_stream<1, 4, 4, kSegLarge, kEpiStatic, HB>(nullptr, T, K, grp, ep, units, stream, x, ldx, c_vis, c_txt);
+}
+
+int gemv_stream_fused(const __half *x, int64_t ldx, int32_t T, int32_t K, int32_t had_block, const GemvGroup &grp,
+                      const Epilogue &ep, float c_vis, float c_txt, hipStream_t stream)
+{
+    if (T < 1 || T > kGemvStreamLdsMaxT || K % 128 != 0 || static_cast<int64_t>(T) * K > kStreamMaxXq || grp.n != 1)
+        return MQUANT_ERR_UNSUPPORTED;
+    switch (had_block) {
+    case 1: return stream_fused_hb<1>(x, ldx, T, K, grp, ep, c_vis, c_txt, stream);
+    case 128: return stream_fused_hb<128>(x, ldx, T, K, grp, ep, c_vis, c_txt, stream);
+    case 512: return stream_fused_hb<512>(x, ldx, T, K, grp, ep, c_vis, c_txt, stream);
+    default: return MQUANT_ERR_UNSUPPORTED;
+    }
 }
 
 template int gemv_stream_dispatch<kEpiStatic>(const int8_t *, int32_t, int32_t, GemvGroup, const Epilogue &, hipStream_t);
