@@ -578,6 +578,7 @@ def bench_decode(b):
     gen = torch.Generator(device="cuda")
     gen.manual_seed(3000)
     streams = [torch.cuda.Stream() for _ in range(4)]
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     wd = wl.workload(3, 1)
     layers = []
     for _ in range(args.decode_layers):
@@ -725,6 +726,15 @@ def bench_decode(b):
             nbytes = K * N / 2 + 2 * N + T * K + 2 * T * N
             per_proj[proj] = {"us": stats(us, 2), "GBps": round(nbytes / med / 1e3, 1),
                               "frac": round(nbytes / med / 1e3 / HBM_PEAK_GBPS, 4)}
+            if T == 1 and not args.no_probes:
+                # the floor of this launch pattern: a kernel that only reads the same weight
+                # buffers (the probe library's read stream), one launch per layer, same graph form
+                def read_pass(src=src, key=key):
+                    for layer in src:
+                        b.probes.hbm_read(layer[key][2], sink)
+                us_r = [m * 1e3 / len(layers) for m in b.time_blocks(b.graph_of(read_pass), args.decode_iters)]
+                per_proj[proj]["read_only_kernel_us"] = round(statistics.median(us_r), 2)
+                per_proj[proj]["read_only_kernel_over_gemv"] = round(statistics.median(us_r) / med, 3)
         res["per_projection_gemv"] = per_proj
         out["per_T"][f"T{T}"] = res
     del layers, fused_layers

@@ -137,6 +137,69 @@ __global__ __launch_bounds__(256) void remap_mask_kernel(
     }
 }
 
+// The same remap for T % 16 == 0 with R output rows per work-group: their R source rows
+// M[perm[i], :] are copied into LDS with 16-byte loads, and every thread then gathers four
+// consecutive output bytes of each row from there.  The index vector is read once per R rows
+// instead of once per row (it is four times the size of a mask row), and the byte gathers hit
+// LDS instead of the memory pipeline.
+template <int R>
+__global__ __launch_bounds__(1024) void remap_mask_rows_kernel(
+    const uint8_t *__restrict__ mask, uint8_t *__restrict__ mask_u,
+    const int32_t *__restrict__ perm, int32_t T)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t rows[];      // R rows of T bytes
+    const int tid = threadIdx.x;
+    for (int32_t i0 = blockIdx.x * R; i0 < T; i0 += gridDim.x * R) {
+        __syncthreads();                                                 // the previous rows are consumed
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (i0 + r < T) {                                            // uniform
+                int32_t pi = perm[i0 + r];
+                pi = (pi < 0 || pi >= T) ? 0 : pi;
+                const uint4 *src = reinterpret_cast<const uint4 *>(mask + static_cast<int64_t>(pi) * T);
+                for (int32_t c = tid; c < T / 16; c += 1024)
+                    *reinterpret_cast<uint4 *>(rows + r * T + c * 16) = src[c];
+            }
+        }
+        __syncthreads();
+        for (int32_t j0 = tid * 4; j0 < T; j0 += 4096) {
+            const int4 pj = *reinterpret_cast<const int4 *>(perm + j0);
+            int32_t p[4] = {pj.x, pj.y, pj.z, pj.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) p[q] = (p[q] < 0 || p[q] >= T) ? 0 : p[q];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (i0 + r < T) {
+                    const uint8_t *row = rows + r * T;
+                    const uint32_t x = static_cast<uint32_t>(row[p[0]]) | (static_cast<uint32_t>(row[p[1]]) << 8) |
+                                       (static_cast<uint32_t>(row[p[2]]) << 16) | (static_cast<uint32_t>(row[p[3]]) << 24);
+                    // every byte -> 1 if non-zero, else 0
+                    const uint32_t nz = ((((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x) & 0x80808080u) >> 7;
+                    *reinterpret_cast<uint32_t *>(mask_u + static_cast<int64_t>(i0 + r) * T + j0) = nz;
+                }
+            }
+        }
+    }
+}
+
+template <int R>
+int launch_remap_rows(const uint8_t *mask, uint8_t *mask_u, const int32_t *perm, int32_t T, hipStream_t stream)
+{
+    const size_t lds = static_cast<size_t>(R) * T;
+    auto kern = remap_mask_rows_kernel<R>;
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                144 * 1024) != hipSuccess)
+            return MQUANT_ERR_HIP;
+        attr_set.store(true, std::memory_order_release);
+    }
+    int64_t blocks = ceil_div(T, R);
+    if (blocks > 8 * kNumCU) blocks = 8 * kNumCU;
+    MQ_LAUNCH(kern, dim3(static_cast<unsigned>(blocks)), dim3(1024), lds, stream, mask, mask_u, perm, T);
+    return launch_status();
+}
+
 }  // namespace
 
 extern "C" int mquant_aifs_permute(const void *x, int64_t ldx, void *x_u, int64_t ldxu,
@@ -167,6 +230,12 @@ extern "C" int mquant_aifs_remap_mask(const uint8_t *mask, uint8_t *mask_u, cons
     if (T == 0) return MQUANT_OK;
     if (!mask || !mask_u || !perm) return MQUANT_ERR_NULL;
     if (!aligned_to(mask_u, 4) || !aligned_to(perm, 16)) return MQUANT_ERR_ALIGNMENT;
+    if (T % 16 == 0 && aligned_to(mask, 16) && T <= 144 * 1024) {
+        hipStream_t hs = static_cast<hipStream_t>(stream);
+        if (8 * static_cast<int64_t>(T) <= 144 * 1024) return launch_remap_rows<8>(mask, mask_u, perm, T, hs);
+        if (4 * static_cast<int64_t>(T) <= 144 * 1024) return launch_remap_rows<4>(mask, mask_u, perm, T, hs);
+        return launch_remap_rows<1>(mask, mask_u, perm, T, hs);
+    }
     dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(T, 4), 256)),
               static_cast<unsigned>(T < 65535 ? T : 65535));
     MQ_LAUNCH(remap_mask_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),

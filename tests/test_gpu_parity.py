@@ -106,6 +106,20 @@ def test_aifs_remap_mask_small(mq, T, spans):
         assert (got == orc.aifs_remap_mask(M, perm).astype(np.uint8)).all()
 
 
+@pytest.mark.parametrize("T,spans", [(1024, [(10, 300), (500, 24), (900, 124)]), (16, [(4, 8)]), (2064, [(0, 2064)]),
+                                     (18448, [(100, 9000)])])
+def test_aifs_remap_mask_staged_rows(mq, T, spans):
+    """T % 16 == 0 takes the kernel that stages source rows in LDS (8, 4 or 1 rows per group
+    depending on T); any non-zero input byte means "may attend" and comes out as 1."""
+    say(f"mask staged rows T={T}")
+    rng = np.random.default_rng(T)
+    perm, _, _ = orc.aifs_build_perm(T, spans)
+    M = rng.choice(np.array([0, 0, 1, 2, 255], dtype=np.uint8), size=(T, T))
+    got = mq.aifs_remap_mask(dev(M), dev(perm)).cpu().numpy()
+    want = orc.aifs_remap_mask(M != 0, perm).astype(np.uint8)
+    assert (got == want).all()
+
+
 def test_aifs_remap_mask_config2(mq):
     """4096 x 4096 causal mask of config 2: equal to the oracle's remap (which
     the CPU tests tie to Eq. (6) and to attention invariance)."""
