@@ -18,6 +18,10 @@ using namespace mquant;
 
 namespace {
 
+// Grid: x walks the 512-channel (1024 for B = 1024) segments of a row, four per work-group
+// (one per wave), y walks the rows.  Row and segment come straight from the block index: an
+// earlier form flattened (row, segment) into one 64-bit index and paid a 64-bit division per
+// segment, half of the kernel's instructions.
 template <int B, bool ABSMAX>
 __global__ __launch_bounds__(256) void hadamard_quant_kernel(
     const __half *__restrict__ x, int64_t ldx, const int32_t *__restrict__ perm,
@@ -25,25 +29,24 @@ __global__ __launch_bounds__(256) void hadamard_quant_kernel(
     int32_t segs_per_row, float *__restrict__ absmax, float q_lo, float q_hi)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t wave0 = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    const int64_t total = static_cast<int64_t>(T) * segs_per_row;
+    const int32_t sidx = static_cast<int32_t>(blockIdx.x) * 4 + static_cast<int32_t>(threadIdx.x >> 6);
     float wave_max = 0.0f;
 
-    for (int64_t seg = wave0; seg < total; seg += static_cast<int64_t>(gridDim.x) * 4) {
-        const int32_t i = static_cast<int32_t>(seg / segs_per_row);
-        const int32_t sidx = static_cast<int32_t>(seg - static_cast<int64_t>(i) * segs_per_row);
-        int32_t src = i;
-        if (perm != nullptr) {
-            src = perm[i];
-            src = (src < 0 || src >= T) ? 0 : src;
-        }
-        Segment<B> sg;
-        sg.load_rotate(x + static_cast<int64_t>(src) * ldx, sidx, K, lane);
-        if constexpr (ABSMAX) {
-            wave_max = sg.absmax(wave_max);
-        } else {
-            sg.quant_store((i < n_vis) ? c_vis : c_txt, xq + static_cast<int64_t>(i) * K, sidx, lane,
-                           q_lo, q_hi);
+    if (sidx < segs_per_row) {                            // wave-uniform
+        for (int32_t i = blockIdx.y; i < T; i += gridDim.y) {
+            int32_t src = i;
+            if (perm != nullptr) {
+                src = perm[i];
+                src = (src < 0 || src >= T) ? 0 : src;
+            }
+            Segment<B> sg;
+            sg.load_rotate(x + static_cast<int64_t>(src) * ldx, sidx, K, lane);
+            if constexpr (ABSMAX) {
+                wave_max = sg.absmax(wave_max);
+            } else {
+                sg.quant_store((i < n_vis) ? c_vis : c_txt, xq + static_cast<int64_t>(i) * K, sidx, lane,
+                               q_lo, q_hi);
+            }
         }
     }
 
@@ -116,10 +119,8 @@ int launch(const void *x, int64_t ldx, const int32_t *perm, int8_t *xq, int32_t 
 {
     const int32_t seg = B > 512 ? B : 512;
     const int32_t segs_per_row = static_cast<int32_t>(ceil_div(K, seg));
-    const int64_t total = static_cast<int64_t>(T) * segs_per_row;
-    int64_t blocks = ceil_div(total, 4);
-    if (blocks > (1 << 20)) blocks = 1 << 20;
-    const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+    const dim3 grid(static_cast<unsigned>(ceil_div(segs_per_row, 4)), static_cast<unsigned>(T < 65535 ? T : 65535)),
+        block(256);
     const __half *xh = static_cast<const __half *>(x);
     const float q_hi = static_cast<float>((1 << (bits - 1)) - 1), q_lo = -static_cast<float>(1 << (bits - 1));
 #define MQ_CASE(BV)                                                                          \
