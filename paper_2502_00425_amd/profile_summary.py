@@ -11,7 +11,8 @@ A counter run cannot happen inside bench.py, so the flow is: run
 
 once per configuration c (each counter in a run of its own; a kernel trace of the same command,
 `rocprofv3 --kernel-trace --stats -f csv -d <dir_t> ...`, is tabulated by
-`python -m paper_2502_00425_amd.profile_summary trace --dir <dir_t>`), then
+`python -m paper_2502_00425_amd.profile_summary trace --dir <dir_t>`; any other `--pmc` run by
+`python -m paper_2502_00425_amd.profile_summary counters --dir <dir>`), then
 
     python -m paper_2502_00425_amd.profile_summary --config <c> --fetch <dir_f> --write <dir_w> \\
         --steps 3 --build-id <id printed by the run> [--md profiles/<name>.md]
@@ -117,7 +118,50 @@ def trace_table(directory: str, projections=None,
     return "\n".join(lines)
 
 
+def counters_table(directory: str, only=("w4a8_", "splitk_", "hadamard_", "permute_rows", "remap_mask",
+                                           "aifs_attention", "w4g128_")) -> str:
+    """Averages per (kernel, launch shape) of every counter a `rocprofv3 --pmc` run collected
+    (each dispatch summed over the counter's instances), one column per counter."""
+    files = glob.glob(os.path.join(directory, "**", "*counter_collection.csv"), recursive=True)
+    if not files:
+        raise SystemExit(f"no *counter_collection.csv under {directory}")
+    per_dispatch = defaultdict(lambda: defaultdict(float))
+    meta = {}
+    names = []
+    for f in files:
+        with open(f, newline="") as fh:
+            for row in csv.DictReader(fh):
+                name = short_name(row["Kernel_Name"])
+                if not name.startswith(only):
+                    continue
+                key = (f, row["Dispatch_Id"])
+                per_dispatch[key][row["Counter_Name"]] += float(row["Counter_Value"])
+                meta[key] = (name, int(row["Grid_Size"]) // max(int(row["Workgroup_Size"]), 1))
+                if row["Counter_Name"] not in names:
+                    names.append(row["Counter_Name"])
+    groups = defaultdict(list)
+    for key, c in per_dispatch.items():
+        groups[meta[key]].append(c)
+    lines = ["| kernel | work-groups | dispatches | " + " | ".join(names) + " |", "|---|---|---|" + "---|" * len(names)]
+    for (name, wgs), cs in sorted(groups.items()):
+        avg = [sum(c.get(n, 0.0) for c in cs) / len(cs) for n in names]
+        lines.append(f"| `{name}` | {wgs} | {len(cs)} | " + " | ".join(f"{v:.4g}" for v in avg) + " |")
+    return "\n".join(lines)
+
+
 def main():
+    if len(sys.argv) > 1 and sys.argv[1] == "counters":
+        ap = argparse.ArgumentParser()
+        ap.add_argument("mode")
+        ap.add_argument("--dir", required=True, help="output directory of the --pmc run")
+        ap.add_argument("--md", default=None)
+        a = ap.parse_args()
+        table = counters_table(a.dir)
+        print(table)
+        if a.md:
+            with open(a.md, "a") as fh:
+                fh.write("\n" + table + "\n")
+        return
     if len(sys.argv) > 1 and sys.argv[1] == "trace":
         ap = argparse.ArgumentParser()
         ap.add_argument("mode")
