@@ -31,7 +31,18 @@ constexpr int kHeadDim = 128;          // the only head size built (28 x 128, 64
 constexpr int kBQ = 128;               // queries per work-group (32 per wave)
 constexpr int kBK = 64;                // keys per tile
 constexpr int kKPitch = 2 * kHeadDim + 16;   // bytes per key row in LDS: rows 4 banks apart
+constexpr int kAhead = 4;               // LDS fragment reads in flight ahead of the MFMA that uses them
 constexpr int kVPitch = 2 * kBK + 16;        // bytes per V^T row (one head channel, 64 keys); 16-byte reads of 16 rows cover the 64 banks once
+
+// The value of the partner lane (lane ^ 32) next to this lane's own: v_permlane32_swap on two
+// copies leaves {low half, low half} and {high half, high half}; no LDS traffic, so fragment
+// reads that are in flight are not waited for.
+__device__ __forceinline__ void halves_of(float x, float &lo, float &hi)
+{
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+    lo = __int_as_float(sw[0]);
+    hi = __int_as_float(sw[1]);
+}
 
 // MFMA 32x32 result register r of lane group g holds row (r/4)*8 + g*4 + r%4.
 __device__ __forceinline__ int acc_row(int r, int g) { return (r >> 2) * 8 + g * 4 + (r & 3); }
@@ -138,7 +149,8 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
     const __half *__restrict__ q, int64_t ldq, const __half *__restrict__ k, int64_t ldk,
     const __half *__restrict__ vt, int32_t Tp, __half *__restrict__ o, int64_t ldo,
     const int32_t *__restrict__ pos, const int32_t *__restrict__ tile_min,
-    const int32_t *__restrict__ tile_max, int32_t T, int32_t group, float scale_log2e)
+    const int32_t *__restrict__ tile_max, int32_t T, int32_t group, int32_t n_kv_heads, int32_t n_qblocks,
+    float scale_log2e)
 {
     __shared__ __attribute__((aligned(16))) uint8_t k_lds2[2][kBK * kKPitch];
     __shared__ __attribute__((aligned(16))) uint8_t v_lds2[2][kHeadDim * kVPitch];
@@ -147,8 +159,14 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
-    const int32_t head = blockIdx.y, kvh = head / group;
-    const int32_t q0 = blockIdx.x * kBQ + wave * 32;
+    // One-dimensional grid, heads fastest, query blocks from the last to the first: in AIFS
+    // order the later blocks of each modality see the most keys, so the long work-groups start
+    // first and the short ones fill the end of the launch; neighbours in the grid are the heads
+    // of one query block, which read the same key tiles.
+    const int32_t n_heads = group * n_kv_heads;
+    const int32_t head = blockIdx.x % n_heads, kvh = head / group;
+    const int32_t qblock = n_qblocks - 1 - blockIdx.x / n_heads;
+    const int32_t q0 = qblock * kBQ + wave * 32;
     const int32_t n_tiles = Tp / kBK;
 
     // ---- this lane's query: position and Q^T fragments
@@ -240,7 +258,12 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
     fetch(tn < n_tiles ? tn : (t < n_tiles ? t : 0));      // unconditional: a harmless re-read at the end
     __syncthreads();
     int buf = 0;
+    // bounds of the current tile's positions; those of the next tile are requested a whole
+    // iteration before they decide a branch (a scalar load in front of its use stalls the wave)
+    int32_t kmin = tile_min[t < n_tiles ? t : 0], kmax = tile_max[t < n_tiles ? t : 0];
     while (t < n_tiles) {
+        const int32_t tn_c = tn < n_tiles ? tn : t;
+        const int32_t kmin_n = tile_min[tn_c], kmax_n = tile_max[tn_c];
         // Registers hold tile tn: into the other buffer, which every wave left at the barrier
         // that ended the previous iteration.  Then request the tile after it.
         stage(buf ^ 1);
@@ -249,7 +272,6 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
         const uint8_t *k_lds = k_lds2[buf], *v_lds = v_lds2[buf];
         const int32_t *pos_lds = pos_lds2[buf];
 
-        const int32_t kmin = tile_min[t], kmax = tile_max[t];
         const bool padded = (t + 1) * kBK > T;             // tile holds keys past the end
         if (kmin <= qmax) {                                // else: masked for all 32 queries of the wave
             // ---- S^T = K Q^T
@@ -258,15 +280,32 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[kb][r] = 0.0f;
-            // the two key blocks alternate: a dependent MFMA pair back to back waits out the pipe
+            // The two key blocks alternate (a dependent MFMA pair back to back waits out the
+            // pipe).  The K fragments run kAhead MFMAs ahead of their use through a rotating
+            // register window: left to the scheduler, every read sits right in front of its
+            // MFMA and each pair of MFMAs waits out a full LDS round trip.
+            auto kfrag = [&](int i) {                      // fragment of MFMA i = ks * 2 + kb
+                return *reinterpret_cast<const v8h *>(k_lds + ((i & 1) * 32 + l32) * kKPitch + g * 16 + (i >> 1) * 32);
+            };
+            v8h fr[kAhead];
 #pragma unroll
-            for (int ks = 0; ks < kHeadDim / 16; ++ks)
+            for (int i = 0; i < kAhead; ++i) fr[i] = kfrag(i);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    const v8h a = *reinterpret_cast<const v8h *>(
-                        k_lds + (kb * 32 + l32) * kKPitch + g * 16 + ks * 32);
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qf[ks], s[kb], 0, 0, 0);
-                }
+            for (int i = 0; i < 2 * (kHeadDim / 16); ++i) {
+                s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[i % kAhead], qf[i >> 1], s[i & 1], 0, 0, 0);
+                if (i + kAhead < 2 * (kHeadDim / 16)) fr[i % kAhead] = kfrag(i + kAhead);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // the first V^T fragments travel while the softmax runs
+            auto vfrag = [&](int i) {                      // fragment of MFMA i = kk * 4 + dt
+                // operand slot j of lane group g is key kk*16 + (j/4)*8 + g*4 + j%4: one
+                // 16-byte read in the chunk order the staging wrote
+                return *reinterpret_cast<const v8h *>(v_lds + ((i & 3) * 32 + l32) * kVPitch + (i >> 2) * 32 + g * 16);
+            };
+#pragma unroll
+            for (int i = 0; i < kAhead; ++i) fr[i] = vfrag(i);
+            __builtin_amdgcn_sched_barrier(0);
             // ---- mask, online softmax
             if (kmax > qmin || padded) {                   // wave-uniform: some (query, key) pair is hidden
 #pragma unroll
@@ -280,7 +319,11 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) m_new = fmaxf(m_new, s[kb][r]);
-            m_new = fmaxf(m_new, __shfl_xor(m_new, 32, 64));     // the query's other 32 keys
+            {
+                float lo, hi;
+                halves_of(m_new, lo, hi);                        // the query's other 32 keys
+                m_new = fmaxf(lo, hi);
+            }
             if (__any(m_new > m_ref + lazy_raw)) {         // also the first visible tile (m_ref = -inf)
                 const float m_use = m_new == -INFINITY ? 0.0f : m_new;
                 const float alpha = __builtin_amdgcn_exp2f((m_ref - m_use) * scale_log2e);   // exp2(-inf) = 0
@@ -302,21 +345,24 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
                     l_add += e;
                     p[kb * 2 + (r >> 3)][r & 7] = static_cast<_Float16>(e);
                 }
-            l_add += __shfl_xor(l_add, 32, 64);
+            {
+                float lo, hi;
+                halves_of(l_add, lo, hi);
+                l_add = lo + hi;
+            }
             l_run += l_add;
-            // ---- O^T += V^T P^T (the four channel blocks alternate)
+            // ---- O^T += V^T P^T (the four channel blocks alternate; same rotating window)
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    // operand slot i of lane group g is key kk*16 + (i/4)*8 + g*4 + i%4: one
-                    // 16-byte read in the chunk order the staging wrote
-                    const v8h a = *reinterpret_cast<const v8h *>(
-                        v_lds + (dt * 32 + l32) * kVPitch + kk * 32 + g * 16);
-                    acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p[kk], acc_o[dt], 0, 0, 0);
-                }
+            for (int i = 0; i < 16; ++i) {
+                acc_o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[i % kAhead], p[i >> 2], acc_o[i & 3], 0, 0, 0);
+                if (i + kAhead < 16) fr[i % kAhead] = vfrag(i + kAhead);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         __syncthreads();                                   // buffer buf is free, buffer buf^1 is published
+        kmin = kmin_n;
+        kmax = kmax_n;
         t = tn;
         tn = tnn;
         buf ^= 1;
@@ -410,9 +456,11 @@ extern "C" int mquant_aifs_attention(const void *q, int64_t ldq, const void *k, 
     int ls = launch_status();
     if (ls != MQUANT_OK) return ls;
     const float scale_log2e = static_cast<float>(1.4426950408889634 / sqrt(static_cast<double>(head_dim)));
-    MQ_LAUNCH(aifs_attention_kernel, dim3(static_cast<unsigned>(ceil_div(T, kBQ)), n_q_heads), dim3(256),
+    const int64_t n_qblocks = ceil_div(T, kBQ);
+    if (n_qblocks * n_q_heads > 0x7fffffff) return MQUANT_ERR_UNSUPPORTED;
+    MQ_LAUNCH(aifs_attention_kernel, dim3(static_cast<unsigned>(n_qblocks * n_q_heads)), dim3(256),
               0, stream, static_cast<const __half *>(q), ldq, static_cast<const __half *>(k), ldk, vt, Tp,
-              static_cast<__half *>(o), ldo, pos, tile_min, tile_max, T, n_q_heads / n_kv_heads,
-              scale_log2e);
+              static_cast<__half *>(o), ldo, pos, tile_min, tile_max, T, n_q_heads / n_kv_heads, n_kv_heads,
+              static_cast<int32_t>(n_qblocks), scale_log2e);
     return launch_status();
 }
