@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
     const __half *__restrict__ vt, int32_t Tp, __half *__restrict__ o, int64_t ldo,
     const int32_t *__restrict__ pos, const int32_t *__restrict__ tile_min,
     const int32_t *__restrict__ tile_max, int32_t T, int32_t group, int32_t n_kv_heads, int32_t n_qblocks,
-    float scale_log2e)
+    int32_t xcds_per_kv, float scale_log2e)
 {
     __shared__ __attribute__((aligned(16))) uint8_t k_lds2[2][kBK * kKPitch];
     __shared__ __attribute__((aligned(16))) uint8_t v_lds2[2][kHeadDim * kVPitch];
@@ -163,9 +163,24 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
     // order the later blocks of each modality see the most keys, so the long work-groups start
     // first and the short ones fill the end of the launch; neighbours in the grid are the heads
     // of one query block, which read the same key tiles.
+    // Work-group ids are dealt round-robin to the 8 XCDs, each with its own L2.  When the
+    // key/value heads divide the XCDs evenly (xcds_per_kv > 0), an XCD serves ONE key/value
+    // head: its resident work-groups then walk the same key tiles at about the same time and
+    // the L2 fetches each tile once for all of them (with heads simply dealt in order every
+    // XCD streams all key/value heads and two thirds of the tile requests hit).
     const int32_t n_heads = group * n_kv_heads;
-    const int32_t head = blockIdx.x % n_heads, kvh = head / group;
-    const int32_t qblock = n_qblocks - 1 - blockIdx.x / n_heads;
+    int32_t head, qblock;
+    if (xcds_per_kv > 0) {
+        const int32_t xcd = blockIdx.x % 8, n = blockIdx.x / 8;
+        const int32_t m = n * xcds_per_kv + xcd % xcds_per_kv;      // item of this key/value head
+        if (m >= n_qblocks * group) return;                         // uniform: whole work-group
+        head = (xcd / xcds_per_kv) * group + m % group;
+        qblock = n_qblocks - 1 - m / group;
+    } else {
+        head = blockIdx.x % n_heads;
+        qblock = n_qblocks - 1 - blockIdx.x / n_heads;
+    }
+    const int32_t kvh = head / group;
     const int32_t q0 = qblock * kBQ + wave * 32;
     const int32_t n_tiles = Tp / kBK;
 
@@ -457,10 +472,13 @@ extern "C" int mquant_aifs_attention(const void *q, int64_t ldq, const void *k, 
     if (ls != MQUANT_OK) return ls;
     const float scale_log2e = static_cast<float>(1.4426950408889634 / sqrt(static_cast<double>(head_dim)));
     const int64_t n_qblocks = ceil_div(T, kBQ);
-    if (n_qblocks * n_q_heads > 0x7fffffff) return MQUANT_ERR_UNSUPPORTED;
-    MQ_LAUNCH(aifs_attention_kernel, dim3(static_cast<unsigned>(n_qblocks * n_q_heads)), dim3(256),
+    const int32_t group = n_q_heads / n_kv_heads;
+    const int32_t xcds_per_kv = 8 % n_kv_heads == 0 ? 8 / n_kv_heads : 0;
+    const int64_t groups = xcds_per_kv > 0 ? 8 * ceil_div(n_qblocks * group, xcds_per_kv) : n_qblocks * n_q_heads;
+    if (groups > 0x7fffffff) return MQUANT_ERR_UNSUPPORTED;
+    MQ_LAUNCH(aifs_attention_kernel, dim3(static_cast<unsigned>(groups)), dim3(256),
               0, stream, static_cast<const __half *>(q), ldq, static_cast<const __half *>(k), ldk, vt, Tp,
-              static_cast<__half *>(o), ldo, pos, tile_min, tile_max, T, n_q_heads / n_kv_heads, n_kv_heads,
-              static_cast<int32_t>(n_qblocks), scale_log2e);
+              static_cast<__half *>(o), ldo, pos, tile_min, tile_max, T, group, n_kv_heads,
+              static_cast<int32_t>(n_qblocks), xcds_per_kv, scale_log2e);
     return launch_status();
 }
