@@ -85,6 +85,12 @@ def tile_indicator_values(T, Hkv, D=128):
     (301, [(5, 100), (150, 7), (290, 11)], 3, 1),  # several visual spans, visual at the very end
     (256, [], 2, 1),                             # text only: plain causal
     (256, [(0, 256)], 2, 1),                     # visual only
+    # work-group -> (head, query block) mappings: key/value heads that do not divide the 8 XCDs
+    # (heads dealt in order), one XCD per key/value head, and a grid with idle work-groups
+    (200, [(16, 100)], 6, 3),
+    (300, [(40, 120), (200, 30)], 16, 8),
+    (130, [(3, 60)], 5, 1),
+    (700, [(100, 400)], 12, 6),
 ])
 def test_attention_small_full(mq, T, spans, Hq, Hkv):
     say(f"attention T={T} spans={spans}")
