@@ -19,7 +19,7 @@ SOURCES = ["aifs.hip", "hadamard_quant.hip", "w4a8_gemm.hip", "w4a8_gemv.hip", "
 # The benchmark's measurement probes: their own shared object, outside the product's ABI.
 PROBES_LIB = os.path.join(LIB_DIR, "libmquant_probes.so")
 PROBES_SOURCES = ["probes.hip"]
-HEADERS = ["mquant_internal.h", "hadamard_segment.h", "w4a8_common.h", "probes.h"]
+HEADERS = ["mquant_internal.h", "hadamard_segment.h", "w4a8_common.h", "lds_dma.h", "probes.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

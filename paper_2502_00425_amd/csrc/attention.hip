@@ -15,6 +15,7 @@
 #include <climits>
 #include <cmath>
 
+#include "lds_dma.h"
 #include "mquant_internal.h"
 
 using namespace mquant;
@@ -30,9 +31,25 @@ typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 constexpr int kHeadDim = 128;          // the only head size built (28 x 128, 64 x 128 in the paper's models)
 constexpr int kBQ = 128;               // queries per work-group (32 per wave)
 constexpr int kBK = 64;                // keys per tile
-constexpr int kKPitch = 2 * kHeadDim + 16;   // bytes per key row in LDS: rows 4 banks apart
 constexpr int kAhead = 4;               // LDS fragment reads in flight ahead of the MFMA that uses them
-constexpr int kVPitch = 2 * kBK + 16;        // bytes per V^T row (one head channel, 64 keys); 16-byte reads of 16 rows cover the 64 banks once
+constexpr int kKTile = kBK * 2 * kHeadDim;   // a key tile in LDS: 64 rows of 256 bytes
+constexpr int kVTile = kHeadDim * 2 * kBK;   // a V^T tile in LDS: 128 rows (head channels) of 128 bytes
+
+// Tiles arrive by LDS-DMA (1 KiB per wave instruction, lane i at offset 16 i), so rows cannot
+// be padded; instead the 16-byte chunks of a row are XOR-swizzled, on the global side of the
+// copy, so that the 16 lanes the LDS serves together (16 consecutive rows, one logical chunk)
+// cover the 64 banks exactly once: key rows are 256 bytes (the full bank space), V^T rows 128.
+__device__ __forceinline__ int k_off(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
+__device__ __forceinline__ int v_off(int d, int chunk) { return d * 128 + ((chunk ^ ((d >> 1) & 7)) << 4); }
+
+// Key order inside the V^T rows: the P V product takes its key index from the score registers
+// (operand slot i of lane group g is key 16 kk + 8 (i / 4) + 4 g + i % 4), so the transpose
+// stores every 16 keys as 0-3, 8-11, 4-7, 12-15 and an operand is one aligned 16-byte chunk.
+__device__ __forceinline__ int vt_key_of_slot(int p)
+{
+    const int x = p & 15;
+    return (p & ~15) | (x < 4 ? x : (x < 8 ? x + 4 : (x < 12 ? x - 4 : x)));
+}
 
 // The value of the partner lane (lane ^ 32) next to this lane's own: v_permlane32_swap on two
 // copies leaves {low half, low half} and {high half, high half}; no LDS traffic, so fragment
@@ -81,11 +98,11 @@ __global__ __launch_bounds__(256) void rope_kernel(__half *__restrict__ x, int64
 
 // -------------------------------------------------------- V^T and tile bounds
 //
-// The P V product wants, per head channel, eight consecutive keys in one MFMA
-// operand register pair, so V goes through a one-off transpose
-// V[T][Hkv*D] -> Vt[Hkv*D][Tp] (Tp = T rounded up to the key tile, tail zeroed:
-// a zero probability times an uninitialised value could be NaN).  The same
-// launch records min and max position of every key tile.
+// The P V product wants, per head channel, the eight keys of an MFMA operand in one
+// 16-byte chunk, so V goes through a one-off transpose V[T][Hkv*D] -> Vt[Hkv*D][Tp]
+// (Tp = T rounded up to the key tile, tail zeroed: a zero probability times an
+// uninitialised value could be NaN; keys inside a row in the order of vt_key_of_slot).
+// The same launch records min and max position of every key tile.
 __global__ __launch_bounds__(256) void vt_kernel(const __half *__restrict__ v, int64_t ldv,
                                                  __half *__restrict__ vt, int32_t T, int32_t Tp,
                                                  int32_t channels, const int32_t *__restrict__ pos,
@@ -111,7 +128,7 @@ __global__ __launch_bounds__(256) void vt_kernel(const __half *__restrict__ v, i
         const int c = half * 32 + r8;                       // channel row of the transposed tile
         __half out[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = tile[c8 + i][c];
+        for (int i = 0; i < 8; ++i) out[i] = tile[vt_key_of_slot(c8 + i)][c];
         *reinterpret_cast<uint4 *>(vt + static_cast<int64_t>(c0 + c) * Tp + t0 + c8) =
             *reinterpret_cast<const uint4 *>(out);
     }
@@ -140,11 +157,15 @@ __global__ __launch_bounds__(256) void vt_kernel(const __half *__restrict__ v, i
 //   P^T             the same registers, as fp16, are the B operand of
 //   O^T += V^T P^T  A = V^T rows (head channels) from LDS; the result again has a lane per
 //                   query, so the running rescale needs no cross-lane traffic.
-// The next tile's K and V^T are requested from memory before the current tile is
-// computed and written to LDS after it.  Tiles whose smallest position exceeds the
-// group's largest query position are skipped altogether (no loads); a wave skips
-// the arithmetic of a tile that is masked for all of its 32 queries and drops the
-// per-element compare on tiles that are visible to all of them.
+// Software pipeline, one tile deep inside a wave: while the exponentials of tile j run on
+// the vector ALU, the matrix core computes the scores of tile j+1 (a second score register
+// set; the two instruction streams are written interleaved and pinned), so of the three
+// parts of a tile -- scores, softmax, P V -- only two are paid in sequence.  Key tiles are
+// therefore fetched one step ahead of value tiles.  Tiles travel global -> LDS by LDS-DMA
+// (no staging registers), two buffers each for K and V^T, one barrier per tile.
+// Tiles whose smallest position exceeds the group's largest query position are skipped
+// altogether (no loads); a wave skips the arithmetic of a tile that is masked for all of its
+// 32 queries and drops the per-element compare on tiles that are visible to all of them.
 __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
     const __half *__restrict__ q, int64_t ldq, const __half *__restrict__ k, int64_t ldk,
     const __half *__restrict__ vt, int32_t Tp, __half *__restrict__ o, int64_t ldo,
@@ -152,22 +173,20 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
     const int32_t *__restrict__ tile_max, int32_t T, int32_t group, int32_t n_kv_heads, int32_t n_qblocks,
     int32_t xcds_per_kv, float scale_log2e)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t k_lds2[2][kBK * kKPitch];
-    __shared__ __attribute__((aligned(16))) uint8_t v_lds2[2][kHeadDim * kVPitch];
+    __shared__ __attribute__((aligned(1024))) uint8_t k_lds2[2][kKTile];
+    __shared__ __attribute__((aligned(1024))) uint8_t v_lds2[2][kVTile];
     __shared__ int32_t pos_lds2[2][kBK];
     __shared__ int32_t wg_qmax_lds[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
-    // One-dimensional grid, heads fastest, query blocks from the last to the first: in AIFS
-    // order the later blocks of each modality see the most keys, so the long work-groups start
-    // first and the short ones fill the end of the launch; neighbours in the grid are the heads
-    // of one query block, which read the same key tiles.
     // Work-group ids are dealt round-robin to the 8 XCDs, each with its own L2.  When the
     // key/value heads divide the XCDs evenly (xcds_per_kv > 0), an XCD serves ONE key/value
     // head: its resident work-groups then walk the same key tiles at about the same time and
     // the L2 fetches each tile once for all of them (with heads simply dealt in order every
-    // XCD streams all key/value heads and two thirds of the tile requests hit).
+    // XCD streams all key/value heads and two thirds of the tile requests hit).  Query blocks
+    // go from the last to the first: in AIFS order the later blocks of each modality see the
+    // most keys, so the long work-groups start first and the short ones fill the end.
     const int32_t n_heads = group * n_kv_heads;
     int32_t head, qblock;
     if (xcds_per_kv > 0) {
@@ -211,50 +230,66 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[dt][r] = 0.0f;
 
-    // ---- tile staging through registers: 4 chunks of K and 4 of V^T per thread
-    v4u kreg[4];                                           // native vectors: HIP's uint4 struct
-    v2u vreg[8];                                           // ends up in scratch here
-    int32_t preg = 0;
-    const __half *kbase = k + kvh * kHeadDim;
-    const __half *vbase = vt + static_cast<int64_t>(kvh) * kHeadDim * Tp;
-    auto fetch = [&](int32_t t) {
-        const int32_t key0 = t * kBK;
+    // ---- tile copies: 16 blocks of 1 KiB per tile, four per wave.  A copy instruction takes a
+    // wave-uniform base (scalar registers) and a 32-bit offset per lane; block i of a wave lies
+    // a fixed stride after block 0, so a lane keeps three offsets in registers and nothing more
+    // (full 64-bit addresses per copy, hoisted out of the loop, spilled to scratch memory).
+    const uint8_t *kbase = reinterpret_cast<const uint8_t *>(k + kvh * kHeadDim);
+    const uint8_t *vbase = reinterpret_cast<const uint8_t *>(vt + static_cast<int64_t>(kvh) * kHeadDim * Tp);
+    const uint32_t k_lds_addr = lds_address(&k_lds2[0][0]), v_lds_addr = lds_address(&v_lds2[0][0]);
+    const int32_t k_row = wave * 4 + (lane >> 4);          // key row of this lane in block 0 (block i: + 16 i)
+    const uint32_t k_chunk = static_cast<uint32_t>(((lane & 15) ^ (k_row & 15)) << 4);
+    const int32_t v_d = wave * 8 + (lane >> 3);            // head channel of this lane in block 0 (block i: + 32 i)
+    const uint32_t v_lane = static_cast<uint32_t>(v_d) * static_cast<uint32_t>(Tp) * 2u +
+                            static_cast<uint32_t>(((lane & 7) ^ ((v_d >> 1) & 7)) << 4);
+    const uint32_t k_pitch = static_cast<uint32_t>(ldk) * 2u;
+    auto dma_k = [&](int32_t t, int b) {                   // rows past T repeat the last row (masked later)
+        const uint8_t *tile = kbase + static_cast<int64_t>(t) * kBK * ldk * 2;
+        const int32_t last = T - 1 - t * kBK;              // last valid row of this tile
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int c = tid + 256 * i, row = c >> 4, col = c & 15;
-            int32_t key = key0 + row;
-            key = key < T ? key : T - 1;
-            kreg[i] = *reinterpret_cast<const v4u *>(kbase + static_cast<int64_t>(key) * ldk + col * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int c = tid + 256 * i, d = c >> 4, col = c & 15;          // 16 chunks of 4 keys per row
-            vreg[i] = *reinterpret_cast<const v2u *>(vbase + static_cast<int64_t>(d) * Tp + key0 + col * 4);
-        }
-        if (tid < kBK) {
-            const int32_t key = key0 + tid;
-            preg = key < T ? pos[key] : INT_MAX;
+            int32_t row = k_row + 16 * i;
+            row = row < last ? row : last;
+            lds_dma16_uniform_base(tile, static_cast<uint32_t>(row) * k_pitch + k_chunk,
+                                   k_lds_addr + b * kKTile + (i * 4 + wave) * 1024);
         }
     };
-    auto stage = [&](int b) {
+    auto dma_v = [&](int32_t t, int b) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int c = tid + 256 * i, row = c >> 4, col = c & 15;
-            *reinterpret_cast<v4u *>(k_lds2[b] + row * kKPitch + col * 16) = kreg[i];
-        }
-        // The 4-key chunks of a row are stored so that the two chunks an MFMA operand needs
-        // (chunks 4 kk + g and 4 kk + 2 + g for lane group g) sit next to each other.
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int c = tid + 256 * i, d = c >> 4, col = c & 15;
-            const int slot = (col & 12) | ((col & 1) << 1) | ((col >> 1) & 1);
-            *reinterpret_cast<v2u *>(v_lds2[b] + d * kVPitch + slot * 8) = vreg[i];
-        }
-        if (tid < kBK) pos_lds2[b][tid] = preg;
+        for (int i = 0; i < 4; ++i)
+            lds_dma16_uniform_base(vbase + (static_cast<int64_t>(i) * 32 * Tp + static_cast<int64_t>(t) * kBK) * 2, v_lane,
+                                   v_lds_addr + b * kVTile + (i * 4 + wave) * 1024);
+    };
+    auto key_pos = [&](int32_t t) -> int32_t {             // threads 0..63: position of key tid of tile t
+        const int32_t key = t * kBK + (tid & 63);
+        return key < T ? pos[key] : INT_MAX;
     };
     auto next_tile = [&](int32_t t) {                     // first tile >= t the group needs, or n_tiles
         while (t < n_tiles && tile_min[t] > wg_qmax) ++t;
         return t;
+    };
+    // LDS fragments: MFMA i of the score product is (ks, kb) = (i / 2, i % 2), of the P V
+    // product (kk, dt) = (i / 4, i % 4); consecutive MFMAs write different accumulators.
+    const int kswz = l32 & 15, vswz = (l32 >> 1) & 7;
+    auto kfrag = [&](const uint8_t *kb_lds, int i) {
+        return *reinterpret_cast<const v8h *>(kb_lds + ((i & 1) * 32 + l32) * 256 + ((((i >> 1) * 2 + g) ^ kswz) << 4));
+    };
+    auto vfrag = [&](const uint8_t *vb_lds, int i) {
+        return *reinterpret_cast<const v8h *>(vb_lds + ((i & 3) * 32 + l32) * 128 + ((((i >> 2) * 2 + g) ^ vswz) << 4));
+    };
+    const v16f zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // scores of one tile on their own (first tile; tiles whose predecessor this wave skips)
+    auto scores = [&](const uint8_t *kb_lds, v16f (&s)[2]) {
+        v8h fr[kAhead];
+#pragma unroll
+        for (int i = 0; i < kAhead; ++i) fr[i] = kfrag(kb_lds, i);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 2 * (kHeadDim / 16); ++i) {
+            s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[i % kAhead], qf[i >> 1], i < 2 ? zero16 : s[i & 1], 0, 0, 0);
+            if (i + kAhead < 2 * (kHeadDim / 16)) fr[i % kAhead] = kfrag(kb_lds, i + kAhead);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     // Running statistics in raw-logit units; the exponent is exp2((s - m_ref) * c) as one
@@ -266,74 +301,40 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
     const float lazy_raw = kLazy / scale_log2e;
     float m_ref = -INFINITY, l_run = 0.0f;
 
-    int32_t t = next_tile(0);                              // tile of the group's own positions at the latest
-    fetch(t < n_tiles ? t : 0);
-    stage(0);
-    int32_t tn = next_tile(t + 1);
-    fetch(tn < n_tiles ? tn : (t < n_tiles ? t : 0));      // unconditional: a harmless re-read at the end
-    __syncthreads();
-    int buf = 0;
-    // bounds of the current tile's positions; those of the next tile are requested a whole
-    // iteration before they decide a branch (a scalar load in front of its use stalls the wave)
-    int32_t kmin = tile_min[t < n_tiles ? t : 0], kmax = tile_max[t < n_tiles ? t : 0];
-    while (t < n_tiles) {
-        const int32_t tn_c = tn < n_tiles ? tn : t;
-        const int32_t kmin_n = tile_min[tn_c], kmax_n = tile_max[tn_c];
-        // Registers hold tile tn: into the other buffer, which every wave left at the barrier
-        // that ended the previous iteration.  Then request the tile after it.
-        stage(buf ^ 1);
-        const int32_t tnn = tn < n_tiles ? next_tile(tn + 1) : n_tiles;
-        fetch(tnn < n_tiles ? tnn : t);
-        const uint8_t *k_lds = k_lds2[buf], *v_lds = v_lds2[buf];
-        const int32_t *pos_lds = pos_lds2[buf];
-
-        const bool padded = (t + 1) * kBK > T;             // tile holds keys past the end
-        if (kmin <= qmax) {                                // else: masked for all 32 queries of the wave
-            // ---- S^T = K Q^T
-            v16f s[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[kb][r] = 0.0f;
-            // The two key blocks alternate (a dependent MFMA pair back to back waits out the
-            // pipe).  The K fragments run kAhead MFMAs ahead of their use through a rotating
-            // register window: left to the scheduler, every read sits right in front of its
-            // MFMA and each pair of MFMAs waits out a full LDS round trip.
-            auto kfrag = [&](int i) {                      // fragment of MFMA i = ks * 2 + kb
-                return *reinterpret_cast<const v8h *>(k_lds + ((i & 1) * 32 + l32) * kKPitch + g * 16 + (i >> 1) * 32);
-            };
-            v8h fr[kAhead];
-#pragma unroll
-            for (int i = 0; i < kAhead; ++i) fr[i] = kfrag(i);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 2 * (kHeadDim / 16); ++i) {
-                s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[i % kAhead], qf[i >> 1], s[i & 1], 0, 0, 0);
-                if (i + kAhead < 2 * (kHeadDim / 16)) fr[i % kAhead] = kfrag(i + kAhead);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            // the first V^T fragments travel while the softmax runs
-            auto vfrag = [&](int i) {                      // fragment of MFMA i = kk * 4 + dt
-                // operand slot j of lane group g is key kk*16 + (j/4)*8 + g*4 + j%4: one
-                // 16-byte read in the chunk order the staging wrote
-                return *reinterpret_cast<const v8h *>(v_lds + ((i & 3) * 32 + l32) * kVPitch + (i >> 2) * 32 + g * 16);
-            };
-#pragma unroll
-            for (int i = 0; i < kAhead; ++i) fr[i] = vfrag(i);
-            __builtin_amdgcn_sched_barrier(0);
+    // One step of the pipeline: softmax and P V of tile `cur` (scores in s_cur, values in V
+    // buffer par, positions in pos buffer par) while the scores of tile `nxt` (keys in K
+    // buffer par ^ 1) go to s_nxt.  On entry a barrier has published those buffers and freed
+    // K buffer par (its scores are done) and V buffer par ^ 1 (its P V product is done).
+    int32_t cur, nxt;
+    int32_t kmin_c, kmax_c, kmin_n, kmax_n;               // bounds of the positions of cur and nxt
+    auto step = [&](v16f (&s_cur)[2], v16f (&s_nxt)[2], const int par) {
+        const int32_t nn = nxt < n_tiles ? next_tile(nxt + 1) : n_tiles;
+        if (nn < n_tiles) dma_k(nn, par);
+        if (nxt < n_tiles) dma_v(nxt, par ^ 1);
+        int32_t preg = INT_MAX;
+        if (tid < kBK && nxt < n_tiles) preg = key_pos(nxt);
+        // bounds of nn: requested a whole step before they decide a branch
+        const int32_t nn_c = nn < n_tiles ? nn : 0;
+        const int32_t kmin_nn = tile_min[nn_c], kmax_nn = tile_max[nn_c];
+        const uint8_t *kb_lds = k_lds2[par ^ 1], *vb_lds = v_lds2[par];
+        const int32_t *pos_lds = pos_lds2[par];
+        const bool need_cur = kmin_c <= qmax;              // else: masked for all 32 queries of the wave
+        const bool need_nxt = nxt < n_tiles && kmin_n <= qmax;
+        const bool padded = (cur + 1) * kBK > T;           // tile holds keys past the end
+        if (need_cur) {
             // ---- mask, online softmax
-            if (kmax > qmin || padded) {                   // wave-uniform: some (query, key) pair is hidden
+            if (kmax_c > qmin || padded) {                 // wave-uniform: some (query, key) pair is hidden
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        if (pos_lds[kb * 32 + acc_row(r, g)] > my_pos) s[kb][r] = -INFINITY;
+                        if (pos_lds[kb * 32 + acc_row(r, g)] > my_pos) s_cur[kb][r] = -INFINITY;
             }
             float m_new = m_ref;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) m_new = fmaxf(m_new, s[kb][r]);
+                for (int r = 0; r < 16; ++r) m_new = fmaxf(m_new, s_cur[kb][r]);
             {
                 float lo, hi;
                 halves_of(m_new, lo, hi);                        // the query's other 32 keys
@@ -352,14 +353,42 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
             const float neg = m_ref == -INFINITY ? 0.0f : -m_ref * scale_log2e;
             float l_add = 0.0f;
             v8h p[4];
+            // `pinned`: the scores pass through an empty asm, which keeps the compiler from
+            // merging these exponentials with the ones of the other branch and hoisting them
+            // in front of both (they belong between the MFMAs of the interleaved branch)
+            auto exp_pair = [&](int e, bool pinned) {      // elements 2e, 2e+1 of the 32 scores of a lane
+                const int kb = e >> 3, r = (e & 7) * 2;
+                float x0 = s_cur[kb][r], x1 = s_cur[kb][r + 1];
+                if (pinned) asm volatile("" : "+v"(x0), "+v"(x1));
+                const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(x0, scale_log2e, neg));
+                const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(x1, scale_log2e, neg));
+                l_add += e0 + e1;
+                p[kb * 2 + (r >> 3)][r & 7] = static_cast<_Float16>(e0);
+                p[kb * 2 + (r >> 3)][(r & 7) + 1] = static_cast<_Float16>(e1);
+            };
+            v8h fr[kAhead];
+            if (need_nxt) {
+                // exponentials of this tile interleaved with the score MFMAs of the next one:
+                // one MFMA, its fragment read, two exponentials per group, order pinned
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                for (int i = 0; i < kAhead; ++i) fr[i] = kfrag(kb_lds, i);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], scale_log2e, neg));
-                    l_add += e;
-                    p[kb * 2 + (r >> 3)][r & 7] = static_cast<_Float16>(e);
+                for (int i = 0; i < 16; ++i) {
+                    s_nxt[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[i % kAhead], qf[i >> 1],
+                                                                          i < 2 ? zero16 : s_nxt[i & 1], 0, 0, 0);
+                    if (i + kAhead < 16) fr[i % kAhead] = kfrag(kb_lds, i + kAhead);
+                    exp_pair(i, true);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) exp_pair(i, false);
+            }
+            // the first V^T fragments travel while the sums are exchanged
+#pragma unroll
+            for (int i = 0; i < kAhead; ++i) fr[i] = vfrag(vb_lds, i);
+            __builtin_amdgcn_sched_barrier(0);
             {
                 float lo, hi;
                 halves_of(l_add, lo, hi);
@@ -371,16 +400,44 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 acc_o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[i % kAhead], p[i >> 2], acc_o[i & 3], 0, 0, 0);
-                if (i + kAhead < 16) fr[i % kAhead] = vfrag(i + kAhead);
+                if (i + kAhead < 16) fr[i % kAhead] = vfrag(vb_lds, i + kAhead);
                 __builtin_amdgcn_sched_barrier(0);
             }
+        } else if (need_nxt) {
+            scores(kb_lds, s_nxt);
         }
-        __syncthreads();                                   // buffer buf is free, buffer buf^1 is published
-        kmin = kmin_n;
-        kmax = kmax_n;
-        t = tn;
-        tn = tnn;
-        buf ^= 1;
+        if (tid < kBK) pos_lds2[par ^ 1][tid] = preg;
+        wait_vmcnt<0>();                                   // K of nn and V^T of nxt have landed
+        __syncthreads();
+        cur = nxt;
+        nxt = nn;
+        kmin_c = kmin_n, kmax_c = kmax_n;
+        kmin_n = kmin_nn, kmax_n = kmax_nn;
+    };
+
+    // ---- prologue: first tile's keys, values and positions, second tile's keys
+    cur = next_tile(0);                                    // exists: every token sees itself
+    nxt = cur < n_tiles ? next_tile(cur + 1) : n_tiles;
+    if (cur < n_tiles) {
+        dma_k(cur, 0);
+        dma_v(cur, 0);
+        if (nxt < n_tiles) dma_k(nxt, 1);
+        if (tid < kBK) pos_lds2[0][tid] = key_pos(cur);
+    }
+    {
+        const int32_t c = cur < n_tiles ? cur : 0, n = nxt < n_tiles ? nxt : 0;
+        kmin_c = tile_min[c], kmax_c = tile_max[c];
+        kmin_n = tile_min[n], kmax_n = tile_max[n];
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+    v16f s_a[2], s_b[2];
+    if (cur < n_tiles && kmin_c <= qmax) scores(k_lds2[0], s_a);
+    __syncthreads();                                       // K buffer 0 is free for the third tile
+    while (cur < n_tiles) {
+        step(s_a, s_b, 0);
+        if (cur >= n_tiles) break;
+        step(s_b, s_a, 1);
     }
 
     // ---- normalise and store: lane = query, registers = head channels (4 consecutive per group)

@@ -29,6 +29,7 @@
 
 #include "hadamard_segment.h"
 #include "mquant_internal.h"
+#include "lds_dma.h"
 #include "w4a8_common.h"
 
 using namespace mquant;
@@ -84,29 +85,6 @@ __global__ __launch_bounds__(256) void prepack_kernel(
 // The DMA loads are issued through inline asm and tracked with explicit
 // s_waitcnt vmcnt(n): the compiler would otherwise wait for every outstanding
 // LDS-DMA before each ds_read and serialise the pipeline.
-
-typedef const void __attribute__((address_space(1))) *global_ptr_t;
-typedef void __attribute__((address_space(3))) *lds_ptr_t;
-
-// 16 bytes per lane, global -> LDS; LDS address = wave-uniform base + lane * 16.
-__device__ __forceinline__ void lds_dma16(const uint8_t *gsrc, uint8_t *lds_wave_base)
-{
-    const uint32_t m0v =
-        __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
-            (lds_ptr_t)lds_wave_base)));
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(m0v), "v"(gsrc)
-                 : "memory", "m0");
-}
-
-// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits [3:0] and [15:14]).
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt range");
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
-}
 
 // The LDS of gfx950 has 64 four-byte banks (256 B per clock): a 16-byte-per-lane read is
 // served 16 lanes at a time, and those 16 lanes -- 16 consecutive rows reading the same
