@@ -24,6 +24,7 @@ namespace {
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef unsigned int v2u __attribute__((ext_vector_type(2)));
@@ -353,18 +354,24 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
             const float neg = m_ref == -INFINITY ? 0.0f : -m_ref * scale_log2e;
             float l_add = 0.0f;
             v8h p[4];
-            // `pinned`: the scores pass through an empty asm, which keeps the compiler from
-            // merging these exponentials with the ones of the other branch and hoisting them
-            // in front of both (they belong between the MFMAs of the interleaved branch)
-            auto exp_pair = [&](int e, bool pinned) {      // elements 2e, 2e+1 of the 32 scores of a lane
+            // The two branches below take the offset from different registers (`neg_alone` is
+            // a copy the compiler cannot see through): written alike, the compiler merges the
+            // exponentials of both and hoists them in front of the branch, out from between
+            // the MFMAs of the interleaved one.
+            float neg_alone = neg;
+            asm volatile("" : "+v"(neg_alone));
+            auto exp_pair = [&](int e, float off) {        // elements 2e, 2e+1 of the 32 scores of a lane
                 const int kb = e >> 3, r = (e & 7) * 2;
-                float x0 = s_cur[kb][r], x1 = s_cur[kb][r + 1];
-                if (pinned) asm volatile("" : "+v"(x0), "+v"(x1));
-                const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(x0, scale_log2e, neg));
-                const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(x1, scale_log2e, neg));
-                l_add += e0 + e1;
-                p[kb * 2 + (r >> 3)][r & 7] = static_cast<_Float16>(e0);
-                p[kb * 2 + (r >> 3)][(r & 7) + 1] = static_cast<_Float16>(e1);
+                const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[kb][r], scale_log2e, off));
+                const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[kb][r + 1], scale_log2e, off));
+                // the denominator sums the probabilities as the P V product sees them (rounded
+                // to fp16): one dot-product instruction per pair instead of two additions
+                v2h ph;
+                ph[0] = static_cast<_Float16>(e0);
+                ph[1] = static_cast<_Float16>(e1);
+                l_add = __builtin_amdgcn_fdot2(ph, v2h{1, 1}, l_add, false);
+                p[kb * 2 + (r >> 3)][r & 7] = ph[0];
+                p[kb * 2 + (r >> 3)][(r & 7) + 1] = ph[1];
             };
             v8h fr[kAhead];
             if (need_nxt) {
@@ -378,12 +385,12 @@ __global__ __launch_bounds__(256, 2) void aifs_attention_kernel(
                     s_nxt[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[i % kAhead], qf[i >> 1],
                                                                           i < 2 ? zero16 : s_nxt[i & 1], 0, 0, 0);
                     if (i + kAhead < 16) fr[i % kAhead] = kfrag(kb_lds, i + kAhead);
-                    exp_pair(i, true);
+                    exp_pair(i, neg);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             } else {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) exp_pair(i, false);
+                for (int i = 0; i < 16; ++i) exp_pair(i, neg_alone);
             }
             // the first V^T fragments travel while the sums are exchanged
 #pragma unroll
