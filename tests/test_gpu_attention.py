@@ -163,11 +163,30 @@ def test_attention_config1_layout_sampled(mq):
     check_attention(mq, q[perm], k[perm], v[perm], perm, Hq, Hkv, rows=rows, what="c1")
 
 
+def test_attention_config4_layout_sampled(mq):
+    """configs[4]: T = 16384, four visual spans of 3072 between five text spans, 28 query heads
+    on 4 key/value heads (256 key tiles, 128 query blocks, seven rounds of work-groups): sampled
+    rows around every modality and span edge of the reordered sequence."""
+    say("attention c4 sampled")
+    rng = np.random.default_rng(11)
+    T, Hq, Hkv = 16384, 28, 4
+    spans = [(800, 3072), (4704, 3072), (8592, 3072), (12488, 3072)]
+    q, k, v = make_qkv(rng, T, Hq, Hkv, q_gain=0.3)
+    perm, _, V = orc.aifs_build_perm(T, spans)
+    inv = np.argsort(perm)
+    edges = [0, 1, 63, 64, 127, 128, V - 1, V, V + 1, T - 2, T - 1]
+    for s0, l in spans:
+        edges += [int(inv[p]) for p in (s0 - 1, s0, s0 + l - 1, s0 + l) if 0 <= p < T]
+    rows = np.unique(np.r_[np.array(edges), rng.choice(T, 16, replace=False)])
+    check_attention(mq, q[perm], k[perm], v[perm], perm, Hq, Hkv, rows=rows, what="c4")
+
+
 @pytest.mark.parametrize("name,T,spans,q_gain", [
     ("configs[1]", 1280, [(16, 1024)], 0.3),
     ("configs[2]", 4096, [(256, 3584)], 0.3),
     ("configs[2] peaked", 4096, [(256, 3584)], 4.0),
     ("four spans", 4096, [(200, 768), (1176, 768), (2148, 768), (3122, 768)], 0.3),
+    ("configs[4]", 16384, [(800, 3072), (4704, 3072), (8592, 3072), (12488, 3072)], 0.3),
 ])
 def test_attention_every_key_tile_is_visible_on_the_config_layouts(mq, name, T, spans, q_gain):
     """One-hot values per key tile: output channel c of a sampled query is the probability mass
