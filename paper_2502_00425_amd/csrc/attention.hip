@@ -40,8 +40,8 @@ constexpr int kVTile = kHeadDim * 2 * kBK;   // a V^T tile in LDS: 128 rows (hea
 // be padded; instead the 16-byte chunks of a row are XOR-swizzled, on the global side of the
 // copy, so that the 16 lanes the LDS serves together (16 consecutive rows, one logical chunk)
 // cover the 64 banks exactly once: key rows are 256 bytes (the full bank space), V^T rows 128.
-__device__ __forceinline__ int k_off(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
-__device__ __forceinline__ int v_off(int d, int chunk) { return d * 128 + ((chunk ^ ((d >> 1) & 7)) << 4); }
+// Chunk c of key row r sits at r * 256 + ((c ^ (r & 15)) << 4), chunk c of V^T row d at
+// d * 128 + ((c ^ ((d >> 1) & 7)) << 4).
 
 // Key order inside the V^T rows: the P V product takes its key index from the score registers
 // (operand slot i of lane group g is key 16 kk + 8 (i / 4) + 4 g + i % 4), so the transpose
