@@ -100,6 +100,28 @@ def test_attention_small_full(mq, T, spans, Hq, Hkv):
     check_attention(mq, q[perm], k[perm], v[perm], perm, Hq, Hkv, what=f"T={T}")
 
 
+def test_attention_seeded_layout_sweep(mq):
+    """Sixteen seeded layouts: random length (1 .. 700), up to three random visual spans, head
+    counts that exercise every work-group mapping; every output against the oracle."""
+    rng = np.random.default_rng(2024)
+    heads = [(1, 1), (2, 1), (4, 2), (6, 3), (8, 8), (7, 1), (5, 5), (12, 4)]
+    for case in range(16):
+        T = int(rng.integers(1, 701))
+        spans, start = [], 0
+        for _ in range(int(rng.integers(0, 4))):
+            if start >= T:
+                break
+            s0 = int(rng.integers(start, T))
+            ln = int(rng.integers(1, T - s0 + 1))
+            spans.append((s0, ln))
+            start = s0 + ln + int(rng.integers(0, 20))
+        Hq, Hkv = heads[case % len(heads)]
+        say(f"attention sweep {case}: T={T} spans={spans} heads={Hq}/{Hkv}")
+        q, k, v = make_qkv(rng, T, Hq, Hkv, q_gain=float(rng.choice([0.3, 1.0, 3.0])))
+        perm, _, _ = orc.aifs_build_perm(T, spans)
+        check_attention(mq, q[perm], k[perm], v[perm], perm, Hq, Hkv, what=f"sweep {case} T={T} {spans} {Hq}/{Hkv}")
+
+
 def test_attention_peaked_softmax_and_ties(mq):
     """Large logits (one key dominates) and repeated positions (ties attend each other)."""
     say("attention peaked / ties")
