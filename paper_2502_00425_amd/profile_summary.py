@@ -112,9 +112,10 @@ def trace_table(directory: str, projections=None,
                 label = projections[seen[kind] % len(projections)]
                 seen[kind] += 1
         groups[(name, wgs, label)].append(us)
-    lines = ["| kernel | linear | work-groups | dispatches | avg us | min us | max us |", "|---|---|---|---|---|---|---|"]
+    lines = ["| kernel | linear | work-groups | dispatches | avg us | median us | min us | max us |", "|---|---|---|---|---|---|---|---|"]
     for (name, wgs, label), v in sorted(groups.items()):
-        lines.append(f"| `{name}` | {label} | {wgs} | {len(v)} | {sum(v) / len(v):.2f} | {min(v):.2f} | {max(v):.2f} |")
+        med = sorted(v)[len(v) // 2]
+        lines.append(f"| `{name}` | {label} | {wgs} | {len(v)} | {sum(v) / len(v):.2f} | {med:.2f} | {min(v):.2f} | {max(v):.2f} |")
     return "\n".join(lines)
 
 
