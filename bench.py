@@ -679,6 +679,17 @@ def bench_decode(b):
                 for proj, (K, N, wp, ws) in layer.items():
                     mq.w4a8_linear_decode(xs[K], wp, ws, N, 0, s_txt, s_txt, 512, out=ys[N])
 
+        def layer_one_launch_grouped_pass():
+            # the same four launches per layer without concatenated weights: q/k/v and gate/up
+            # keep their own buffers and outputs and share the rotate+quant of their launch
+            for layer in layers:
+                mq.w4a8_linear_decode_grouped(xs[3584], [(layer[p][2], layer[p][3], layer[p][1], ys_multi[i][layer[p][1]])
+                                                         for i, p in enumerate(("q", "k", "v"))], 0, s_txt, s_txt, 512)
+                mq.w4a8_linear_decode_grouped(xs[3584], [(layer["o"][2], layer["o"][3], 3584, ys[3584])], 0, s_txt, s_txt, 512)
+                mq.w4a8_linear_decode_grouped(xs[3584], [(layer[p][2], layer[p][3], layer[p][1], ys_multi[i][layer[p][1]])
+                                                         for i, p in enumerate(("gate", "up"))], 0, s_txt, s_txt, 512)
+                mq.w4a8_linear_decode_grouped(xs[18944], [(layer["down"][2], layer["down"][3], 3584, ys[3584])], 0, s_txt, s_txt, 512)
+
         def gemv_streams_pass():
             # Kernel throughput when launches overlap: the GEMVs here have no data dependence
             # on each other (own input and output buffers), so four independent stream chains
@@ -703,6 +714,7 @@ def bench_decode(b):
         if T <= 4:
             legs.append(("quant+gemv_one_launch", fused_linear_pass))
             legs.append(("layer_4_one_launch_linears", layer_one_launch_pass))
+            legs.append(("layer_4_one_launch_grouped", layer_one_launch_grouped_pass))
         for name, fn in legs + [("gemv_only", gemv_only_pass),
                                 ("gemv_only_fused_qkv_gateup", gemv_fused_pass),
                                 ("gemv_only_grouped_4_launches", gemv_grouped_pass),

@@ -368,7 +368,9 @@ int mquant_w4a8_linear_prefill_static(const void *x_dev, int64_t ldx, const int3
  * mquant_hadamard_quant_act, no gather) inside the weight-streaming GEMV, then
  * the fused dequantisation.  Equivalent to mquant_hadamard_quant_act followed by
  * mquant_w4a8_gemm, bit for bit; saves the separate front-end launch, which at
- * decode costs about as much as a small GEMV.
+ * decode costs about as much as a small GEMV.  Every work-group rotates the T rows
+ * itself, so the saving holds for T = 1 (7B shapes: 3.7 against 5.7 us for K = N = 3584,
+ * even for K = 18944); from T = 2 on the two separate calls are the faster form.
  *   x_dev : fp16 [T, K], leading dimension ldx (multiple of 8), 16-byte aligned
  *   had_block : 1, 128 or 512 (ERR_UNSUPPORTED otherwise, also for T > 4 and for
  *               T * (K + 16) > 150 KiB, the LDS copy of the quantized rows)
@@ -378,6 +380,26 @@ int mquant_w4a8_linear_decode(const void *x_dev, int64_t ldx, const uint8_t *w_p
                               const void *w_scale_dev, void *y_dev, int64_t ldy, int32_t T, int32_t N,
                               int32_t K, int32_t n_vis, float s_vis, float s_txt, int32_t had_block,
                               mquant_stream_t stream);
+
+/*
+ * DEVICE.  mquant_w4a8_linear_decode for several linears that share their input
+ * (q/k/v, gate/up of a decoder layer) in ONE launch (Sec. 3.2 rotation, Eq. (2)-(3)
+ * quantizer, Sec. 4 GEMV): the T rows of x are rotated and quantized once per
+ * work-group, then every linear l gets
+ *     y_l[i, n] = fp16( (float(sum_k xq[i, k] * wq_l[n, k]) * s_i) * float(w_scale_l[n]) ),
+ * bit for bit what mquant_hadamard_quant_act followed by mquant_w4a8_gemm gives for
+ * each of them.  A decoder layer then takes four launches (qkv, o, gate/up, down).
+ *   x_dev    : fp16 [T, K], leading dimension ldx (multiple of 8), 16-byte aligned; T <= 4
+ *   lin_host : HOST array of n_linear (<= 4, ERR_UNSUPPORTED beyond) descriptors; the
+ *              outputs must not overlap
+ * Errors: as mquant_w4a8_linear_decode.  T == 0 or n_linear == 0 is a no-op; a linear
+ * with N == 0 is skipped.  Shapes beyond the one-launch kernel's range (T * K > 80 KiB)
+ * run as one mquant_w4a8_linear_decode launch per linear.
+ */
+int mquant_w4a8_linear_decode_grouped(const void *x_dev, int64_t ldx, int32_t T, int32_t K,
+                                      int32_t n_vis, float s_vis, float s_txt, int32_t had_block,
+                                      const mquant_linear_t *lin_host, int32_t n_linear,
+                                      mquant_stream_t stream);
 
 /* -------------------------------------------------------------------------
  * Attention on AIFS-ordered tokens (Sec. 3.1, Eq. (5)-(6)) and rotary position

@@ -32,6 +32,7 @@ EXPORTS = (
     "mquant_hadamard_quant_act_bits", "mquant_static_scale_from_absmax", "mquant_tune_set",
     "mquant_build_id",
     "mquant_w4a8_linear_decode", "mquant_w4a8_linear_prefill_static", "mquant_w4a8_gemv_grouped",
+    "mquant_w4a8_linear_decode_grouped",
     "mquant_w4g128_prepacked_bytes", "mquant_w4g128_prepack", "mquant_w4g128_gemm",
 )
 
@@ -90,6 +91,7 @@ def _load() -> ctypes.CDLL:
     lib.mquant_w4a8_linear_prefill_static.argtypes = [p, i64, p, p, p, p, i64, i32, i32, i32, i32, f32, f32,
                                                       i32, p]
     lib.mquant_w4a8_gemv_grouped.argtypes = [p, i32, i32, i32, f32, f32, p, i32, p]
+    lib.mquant_w4a8_linear_decode_grouped.argtypes = [p, i64, i32, i32, i32, f32, f32, i32, p, i32, p]
     lib.mquant_rope_apply.argtypes = [p, i64, p, i32, i32, i32, ctypes.c_double, p]
     lib.mquant_aifs_attention_workspace_bytes.restype = i64
     lib.mquant_aifs_attention_workspace_bytes.argtypes = [i32, i32, i32]
@@ -437,6 +439,22 @@ def w4a8_linear_decode(x, w_prepacked, w_scale, N: int, n_vis: int, s_vis: float
                                          out.stride(0), T, N, K, n_vis, s_vis, s_txt, had_block,
                                          _stream()), "mquant_w4a8_linear_decode")
     return out
+
+
+def w4a8_linear_decode_grouped(x, linears, n_vis: int, s_vis: float, s_txt: float, had_block: int):
+    """x fp16 [T <= 4, K]; linears: sequence of (w_prepacked, w_scale, N, out) sharing x.
+    One launch rotates and quantizes x and computes every out [T, N]."""
+    T, K = x.shape
+    _rows(x, "x")
+    arr = (Linear * max(len(linears), 1))()
+    for i, (wp, ws, N, out) in enumerate(linears):
+        _rows(out, "y"), _dense(ws, "w_scale")
+        arr[i].w_prepacked_dev, arr[i].w_scale_dev, arr[i].y_dev = _dp(wp), _dp(ws), _dp(out)
+        arr[i].ldy, arr[i].N = out.stride(0), N
+    _check(lib.mquant_w4a8_linear_decode_grouped(_dp(x), x.stride(0), T, K, n_vis, s_vis, s_txt, had_block,
+                                                 ctypes.cast(arr, ctypes.c_void_p), len(linears),
+                                                 _stream()), "mquant_w4a8_linear_decode_grouped")
+    return [l[3] for l in linears]
 
 
 def w4g128_prepacked_bytes(N: int, K: int) -> int:

@@ -138,9 +138,11 @@ struct GemvGroup {
 // True when the streaming kernel handles this shape (else the callers use the tile kernel).
 bool gemv_stream_takes(int32_t T, int32_t K, int64_t n_tiles);
 
-// One linear, front end (rotation with Hadamard block had_block in {1, 128, 512} + static
-// quantizer) inside the launch.  MQUANT_ERR_UNSUPPORTED when the shape is outside the kernel's
-// range: nothing was launched and the caller takes another path.
+// The linears of a group (one, or several sharing their input), front end (rotation with
+// Hadamard block had_block in {1, 128, 512} + static quantizer) inside the launch.
+// MQUANT_ERR_UNSUPPORTED when the shape is outside the kernel's range
+// (gemv_stream_fused_takes): nothing was launched and the caller takes another path.
+bool gemv_stream_fused_takes(int32_t T, int32_t K, int32_t had_block);
 int gemv_stream_fused(const __half *x, int64_t ldx, int32_t T, int32_t K, int32_t had_block, const GemvGroup &grp,
                       const Epilogue &ep, float c_vis, float c_txt, hipStream_t stream);
 

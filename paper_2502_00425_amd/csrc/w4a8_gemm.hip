@@ -1206,3 +1206,61 @@ extern "C" int mquant_w4a8_linear_decode(const void *x, int64_t ldx, const uint8
     default: return launch_decode_fused<512>(xh, ldx, wpp, wsc, yh, ldy, T, N, K, ep, c_vis, c_txt, stream_h);
     }
 }
+
+extern "C" int mquant_w4a8_linear_decode_grouped(const void *x, int64_t ldx, int32_t T, int32_t K,
+                                                 int32_t n_vis, float s_vis, float s_txt,
+                                                 int32_t had_block, const mquant_linear_t *lin,
+                                                 int32_t n_linear, mquant_stream_t stream)
+{
+    if (T < 0 || K < 0 || n_linear < 0) return MQUANT_ERR_BAD_SHAPE;
+    if (T > kDecodeFusedMaxT || n_linear > kGemvMaxGroup) return MQUANT_ERR_UNSUPPORTED;
+    if (had_block != 1 && had_block != 128 && had_block != 512) return MQUANT_ERR_UNSUPPORTED;
+    if (K % kPackK != 0 || K > kMaxK || K % had_block != 0) return MQUANT_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(T) * (K + 16) > 150 * 1024) return MQUANT_ERR_UNSUPPORTED;
+    if (n_vis < 0 || n_vis > T) return MQUANT_ERR_BAD_SHAPE;
+    if (!(s_vis > 0.0f) || !(s_txt > 0.0f) || !isfinite(s_vis) || !isfinite(s_txt))
+        return MQUANT_ERR_BAD_SHAPE;
+    if (n_linear > 0 && !lin) return MQUANT_ERR_NULL;
+    for (int32_t i = 0; i < n_linear; ++i) {
+        if (lin[i].N < 0) return MQUANT_ERR_BAD_SHAPE;
+        if (lin[i].N > 0 && T > 0 && lin[i].ldy < lin[i].N) return MQUANT_ERR_BAD_SHAPE;
+    }
+    if (T == 0 || n_linear == 0) return MQUANT_OK;
+    if (K == 0) return MQUANT_ERR_UNSUPPORTED;
+    if (ldx < K) return MQUANT_ERR_BAD_SHAPE;
+    if (!x) return MQUANT_ERR_NULL;
+    if (ldx % 8 != 0 || !aligned_to(x, 16)) return MQUANT_ERR_ALIGNMENT;
+    GemvGroup grp = {};
+    for (int32_t i = 0; i < n_linear; ++i) {
+        if (lin[i].N == 0) continue;
+        if (!lin[i].w_prepacked_dev || !lin[i].w_scale_dev || !lin[i].y_dev) return MQUANT_ERR_NULL;
+        if (!aligned_to(lin[i].w_prepacked_dev, 16) || !aligned_to(lin[i].w_scale_dev, 2) ||
+            !aligned_to(lin[i].y_dev, 2))
+            return MQUANT_ERR_ALIGNMENT;
+        GemvProblem &p = grp.p[grp.n++];
+        p.wp = reinterpret_cast<const uint4 *>(lin[i].w_prepacked_dev);
+        p.w_scale = static_cast<const __half *>(lin[i].w_scale_dev);
+        p.y = static_cast<__half *>(lin[i].y_dev);
+        p.acc_out = nullptr;
+        p.ldy = lin[i].ldy;
+        p.N = lin[i].N;
+    }
+    if (grp.n == 0) return MQUANT_OK;
+    if (gemv_stream_fused_takes(T, K, had_block)) {
+        const double rb = sqrt(static_cast<double>(had_block));
+        const float c_vis = static_cast<float>(1.0 / (static_cast<double>(s_vis) * rb));
+        const float c_txt = static_cast<float>(1.0 / (static_cast<double>(s_txt) * rb));
+        Epilogue ep = {};
+        ep.n_vis = n_vis, ep.s_vis = s_vis, ep.s_txt = s_txt, ep.K = K;
+        return gemv_stream_fused(static_cast<const __half *>(x), ldx, T, K, had_block, grp, ep, c_vis, c_txt,
+                                 static_cast<hipStream_t>(stream));
+    }
+    // outside the streaming kernel's range: one launch per linear
+    for (int32_t i = 0; i < grp.n; ++i) {
+        const int st = mquant_w4a8_linear_decode(x, ldx, reinterpret_cast<const uint8_t *>(grp.p[i].wp),
+                                                 grp.p[i].w_scale, grp.p[i].y, grp.p[i].ldy, T, grp.p[i].N, K,
+                                                 n_vis, s_vis, s_txt, had_block, stream);
+        if (st != MQUANT_OK) return st;
+    }
+    return MQUANT_OK;
+}

@@ -503,38 +503,55 @@ int gemv_stream_dispatch(const int8_t *xq, int32_t T, int32_t K, GemvGroup grp, 
     return launch_stream_nx<1, 4, 4, EPI>(xq, T, K, grp, ep, units, stream);
 }
 
-// The one-launch decode linear on the streaming kernel; ERR_UNSUPPORTED when the shape is
-// outside its range (the caller then uses the tile kernel's fused form).
+// The one-launch decode linear on the streaming kernel (one linear, or several that share
+// their input); ERR_UNSUPPORTED when the shape is outside its range (the caller then takes
+// another path).
 template <int HB>
 static int stream_fused_hb(const __half *x, int64_t ldx, int32_t T, int32_t K, GemvGroup grp, const Epilogue &ep,
                            float c_vis, float c_txt, hipStream_t stream)
 {
     constexpr int kSegSmall = 2, kSegLarge = 10;                 // segments per wave the kernel is compiled for
-    const int64_t tiles = ceil_div(grp.p[0].N, kPackN);
+    int64_t tiles = 0;
+    for (int32_t i = 0; i < grp.n; ++i) tiles += ceil_div(grp.p[i].N, kPackN);
     const bool halves = tiles < 2 * kNumCU;
-    grp.p[0].units = static_cast<int32_t>(tiles * (halves ? 2 : 1));
-    const int32_t units = grp.p[0].units;
+    int64_t total = 0;
+    for (int32_t i = 0; i < grp.n; ++i) {
+        grp.p[i].units = static_cast<int32_t>(ceil_div(grp.p[i].N, kPackN) * (halves ? 2 : 1));
+        total += grp.p[i].units;
+    }
+    if (total <= 0 || total > 0x7fffffff) return MQUANT_ERR_BAD_SHAPE;
+    const int32_t units = static_cast<int32_t>(total);
     const int64_t segs = static_cast<int64_t>(T) * ceil_div(K, 512);
     if (segs > kSegLarge * 4) return MQUANT_ERR_UNSUPPORTED;
     const bool small = segs <= kSegSmall * 4;
+    // Every work-group rotates all segments itself, about half a microsecond per segment and
+    // wave, so the few-tile matrices (whose work-groups are alone on their compute unit) take
+    // more waves than the plain stream does: measured at T = 1 on the 7B shapes, 3584 -> 3584
+    // 3.87 -> 3.65 us with eight waves, 18944 -> 3584 11.1 -> 9.9 us with sixteen; with many
+    // output tiles (3584 -> 37888) four waves stay ahead.
     if (halves) {
-        if (small) return launch_stream<2, 4, 8, kSegSmall, kEpiStatic, HB>(nullptr, T, K, grp, ep, units, stream, x, ldx, c_vis, c_txt);
-        return launch_stream<2, 4, 8, kSegLarge, kEpiStatic, HB>(nullptr, T, K, grp, ep, units, stream, x, ldx, c_vis, c_txt);
+        if (small) return launch_stream<2, 8, 4, 1, kEpiStatic, HB>(nullptr, T, K, grp, ep, units, stream, x, ldx, c_vis, c_txt);
+        return launch_stream<2, 16, 2, 3, kEpiStatic, HB>(nullptr, T, K, grp, ep, units, stream, x, ldx, c_vis, c_txt);
     }
     if (small) return launch_stream<1, 4, 4, kSegSmall, kEpiStatic, HB>(nullptr, T, K, grp, ep, units, stream, x, ldx, c_vis, c_txt);
     return launch_stream<1, 4, 4, kSegLarge, kEpiStatic, HB>(nullptr, T, K, grp, ep, units, stream, x, ldx, c_vis, c_txt);
 }
 
+bool gemv_stream_fused_takes(int32_t T, int32_t K, int32_t had_block)
+{
+    if (T < 1 || T > kGemvStreamLdsMaxT || K % 128 != 0 || static_cast<int64_t>(T) * K > kStreamMaxXq) return false;
+    if (static_cast<int64_t>(T) * ceil_div(K, 512) > 40) return false;
+    return had_block == 1 || had_block == 128 || had_block == 512;
+}
+
 int gemv_stream_fused(const __half *x, int64_t ldx, int32_t T, int32_t K, int32_t had_block, const GemvGroup &grp,
                       const Epilogue &ep, float c_vis, float c_txt, hipStream_t stream)
 {
-    if (T < 1 || T > kGemvStreamLdsMaxT || K % 128 != 0 || static_cast<int64_t>(T) * K > kStreamMaxXq || grp.n != 1)
-        return MQUANT_ERR_UNSUPPORTED;
+    if (!gemv_stream_fused_takes(T, K, had_block) || grp.n < 1) return MQUANT_ERR_UNSUPPORTED;
     switch (had_block) {
     case 1: return stream_fused_hb<1>(x, ldx, T, K, grp, ep, c_vis, c_txt, stream);
     case 128: return stream_fused_hb<128>(x, ldx, T, K, grp, ep, c_vis, c_txt, stream);
-    case 512: return stream_fused_hb<512>(x, ldx, T, K, grp, ep, c_vis, c_txt, stream);
-    default: return MQUANT_ERR_UNSUPPORTED;
+    default: return stream_fused_hb<512>(x, ldx, T, K, grp, ep, c_vis, c_txt, stream);
     }
 }
 

@@ -110,6 +110,13 @@ int main()
             lin[n - 1].y_dev = nullptr;
             CHECK(mquant_w4a8_gemv_grouped(Pi8, 1, 128, 0, 1.0f, 1.0f, lin, n, nullptr) == MQUANT_ERR_NULL);
             CHECK(mquant_w4a8_gemv_grouped(Pi8, 0, 128, 0, 1.0f, 1.0f, lin, n, nullptr) == MQUANT_OK);
+            CHECK(mquant_w4a8_linear_decode_grouped(P, 512, 1, 512, 0, 1.0f, 1.0f, 512, lin, n, nullptr) == MQUANT_ERR_NULL);
+            lin[n - 1].y_dev = Q;
+            lin[n - 1].ldy = 32;
+            CHECK(mquant_w4a8_linear_decode_grouped(P, 512, 1, 512, 0, 1.0f, 1.0f, 512, lin, n, nullptr) == MQUANT_ERR_BAD_SHAPE);
+            lin[n - 1].ldy = 64;
+            CHECK(mquant_w4a8_linear_decode_grouped(P, 512, 0, 512, 0, 1.0f, 1.0f, 512, lin, n, nullptr) == MQUANT_OK);
+            CHECK(mquant_w4a8_linear_decode_grouped(P, 512, 5, 512, 0, 1.0f, 1.0f, 512, lin, n, nullptr) == MQUANT_ERR_UNSUPPORTED);
             free(lin);
         }
         CHECK(mquant_w4a8_gemv_grouped(Pi8, 1, 128, 0, 1.0f, 1.0f, nullptr, 5, nullptr) == MQUANT_ERR_UNSUPPORTED);

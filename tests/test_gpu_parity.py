@@ -718,6 +718,67 @@ def test_fused_decode_linear_argument_errors(mq):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("T,K,B,Ns", [(1, 3584, 512, (3584, 512, 512)), (4, 3584, 512, (18944, 18944)),
+                                      (3, 1024, 128, (40, 0, 200, 72)), (2, 8192, 128, (8192, 1024, 1024)),
+                                      (1, 18944, 512, (3584,)), (4, 29568, 128, (264, 96)), (2, 640, 1, (520, 24))])
+def test_fused_decode_grouped_equals_the_oracle_per_linear(mq, T, K, B, Ns):
+    """Rotate + quantize once, then several linears that share the input, all in one launch
+    (q/k/v; gate/up): the fp16 bits of every output of every linear against the oracle's whole
+    path, and against the single-linear entry; padding columns untouched.  (4, 29568) is past
+    the one-launch kernel's range and runs as one launch per linear."""
+    say(f"fused grouped decode T={T} K={K} B={B} Ns={Ns}")
+    rng = np.random.default_rng(T * 977 + K + B + len(Ns))
+    x = (rng.standard_normal((T, K)) * rng.uniform(0.5, 3.0, size=(T, 1))).astype(np.float16)
+    V = min(T, 1)
+    u = orc.hadamard_rotate(x, B)
+    s_vis = float(orc.static_scale_from_absmax(np.abs(u).max(), B))
+    s_txt = s_vis * 0.8
+    lin, want = [], []
+    for N in Ns:
+        packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+        w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+        out = torch.full((T, N + 8), 3.0, dtype=torch.float16, device="cuda")
+        wp = mq.w4_prepack(dev(packed)) if N else torch.empty(0, dtype=torch.uint8, device="cuda")
+        lin.append((wp, dev(w_scale), N, out[:, :N]))
+        want.append(orc.w4a8_linear(x, [(0, V)], packed, w_scale, s_vis, s_txt, B)["y"] if N
+                    else np.zeros((T, 0), dtype=np.float16))
+    xd = dev(x)
+    mq.w4a8_linear_decode_grouped(xd, lin, V, s_vis, s_txt, B)
+    torch.cuda.synchronize()
+    for (wp, ws, N, out), w in zip(lin, want):
+        assert (out.cpu().numpy().view(np.uint16) == w.view(np.uint16)).all(), f"N={N}"
+        if N:
+            assert torch.equal(mq.w4a8_linear_decode(xd, wp, ws, N, V, s_vis, s_txt, B), out)
+        buf = out._base if out._base is not None else out
+        assert bool((buf[:, N:] == 3.0).all())
+
+
+def test_fused_decode_grouped_argument_errors(mq):
+    import ctypes
+    P = 0x1000
+    lin = (mq.Linear * 5)()
+    for i in range(5):
+        lin[i].w_prepacked_dev, lin[i].w_scale_dev, lin[i].y_dev, lin[i].ldy, lin[i].N = P, P, P, 64, 64
+    lp = ctypes.cast(lin, ctypes.c_void_p)
+    f = mq.lib.mquant_w4a8_linear_decode_grouped
+    assert f(P, 512, 1, 512, 0, 1.0, 1.0, 512, lp, 5, None) == mq.ERR_UNSUPPORTED     # more than four linears
+    assert f(P, 512, 5, 512, 0, 1.0, 1.0, 512, lp, 2, None) == mq.ERR_UNSUPPORTED     # more than four rows
+    assert f(P, 512, 1, 512, 0, 1.0, 1.0, 256, lp, 2, None) == mq.ERR_UNSUPPORTED     # Hadamard block
+    assert f(P, 512, 1, 640, 0, 1.0, 1.0, 512, lp, 2, None) == mq.ERR_UNSUPPORTED     # K % block
+    assert f(None, 512, 1, 512, 0, 1.0, 1.0, 512, lp, 2, None) == mq.ERR_NULL
+    assert f(P, 512, 1, 512, 0, 1.0, 1.0, 512, None, 2, None) == mq.ERR_NULL
+    assert f(P, 512, 1, 512, 2, 1.0, 1.0, 512, lp, 2, None) == mq.ERR_BAD_SHAPE       # n_vis > T
+    assert f(P, 512, 1, 512, 0, 1.0, -1.0, 512, lp, 2, None) == mq.ERR_BAD_SHAPE
+    assert f(P, 256, 1, 512, 0, 1.0, 1.0, 512, lp, 2, None) == mq.ERR_BAD_SHAPE       # ldx < K
+    assert f(P, 516, 1, 512, 0, 1.0, 1.0, 512, lp, 2, None) == mq.ERR_ALIGNMENT       # ldx % 8
+    lin[1].ldy = 32
+    assert f(P, 512, 1, 512, 0, 1.0, 1.0, 512, lp, 2, None) == mq.ERR_BAD_SHAPE       # ldy < N
+    lin[1].ldy, lin[1].y_dev = 64, None
+    assert f(P, 512, 1, 512, 0, 1.0, 1.0, 512, lp, 2, None) == mq.ERR_NULL
+    assert f(P, 512, 0, 512, 0, 1.0, 1.0, 512, lp, 2, None) == mq.OK                  # T == 0
+    assert f(P, 512, 1, 512, 0, 1.0, 1.0, 512, lp, 0, None) == mq.OK
+
+
 def test_gemm_seeded_shape_sweep(mq):
     """Thirty seeded shapes across the dispatch boundaries (GEMV / both GEMM tiles / row slabs for
     K % 128 != 0, one k-block, single channels, N not a multiple of 8): accumulators bit for bit."""
