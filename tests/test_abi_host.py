@@ -228,6 +228,7 @@ def test_tune_hook_validates_and_resets():
     assert f(mq.TUNE_GEMM_TILE, -2) == mq.ERR_BAD_SHAPE
     assert f(mq.TUNE_GEMM_NOSPLIT, 2) == mq.ERR_BAD_SHAPE
     assert f(mq.TUNE_G128_TILE, 2) == mq.ERR_BAD_SHAPE
+    assert f(mq.TUNE_GEMV_VARIANT, 4) == mq.ERR_BAD_SHAPE
     # NOSPLIT changes the workspace a long-K, few-tile shape asks for; setting it back restores it
     base = mq.w4a8_workspace_bytes(300, 520, 8192)
     assert base > 0
