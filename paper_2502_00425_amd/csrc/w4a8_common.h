@@ -150,4 +150,10 @@ template <int EPI>
 int gemv_stream_dispatch(const int8_t *xq, int32_t T, int32_t K, GemvGroup grp, const Epilogue &ep,
                          hipStream_t stream);
 
+// The tile GEMV kernel (every decode shape the streaming kernels do not take) for the same
+// kind of group; defined next to the kernel in w4a8_gemm.hip.
+template <int EPI>
+int gemv_tile_dispatch(const int8_t *xq, int32_t T, int32_t K, GemvGroup grp, const Epilogue &ep,
+                       hipStream_t stream);
+
 }  // namespace mquant

@@ -494,13 +494,26 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(
 // 16 bytes -- at T = 16 four times the cache lines of the 1 KiB weight load next to it;
 // staged, the wave reads each row's 256 bytes of the batch once, 16 lanes per row, and
 // picks the fragments out of LDS (row pitch 272 bytes: conflict free).
+//
+// Several linears that share xq (q/k/v, gate/up) can go into one launch: the grid is the
+// concatenation of their tiles (units = 32-channel tiles of each problem).
 template <int NWAVES, int KT, int EPI, int AROWS>
 __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
-    const int8_t *__restrict__ xq, const uint4 *__restrict__ wp, const __half *__restrict__ w_scale,
-    __half *__restrict__ y, int64_t ldy, int32_t *__restrict__ acc_out, int32_t T, int32_t N,
-    int32_t K, Epilogue ep)
+    const int8_t *__restrict__ xq, GemvGroup grp, int32_t T, int32_t K, Epilogue ep)
 {
     typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+    // which linear of the group, which tile of it
+    int32_t pi = 0, ntile = blockIdx.x;
+    while (pi + 1 < grp.n && ntile >= grp.p[pi].units) {
+        ntile -= grp.p[pi].units;
+        ++pi;
+    }
+    const uint4 *__restrict__ wp = grp.p[pi].wp;
+    const __half *__restrict__ w_scale = grp.p[pi].w_scale;
+    __half *__restrict__ y = grp.p[pi].y;
+    int32_t *__restrict__ acc_out = grp.p[pi].acc_out;
+    const int64_t ldy = grp.p[pi].ldy;
+    const int32_t N = grp.p[pi].N;
     constexpr int kPatchPitch = KT * 64 + 16;
     constexpr int kPatchBytes = AROWS * kPatchPitch;
     constexpr int kWaveBytes = kPatchBytes > 4096 ? kPatchBytes : 4096;
@@ -511,7 +524,6 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
     const int wave = threadIdx.x >> 6;
     const int l32 = lane & 31;
     const int g = lane >> 5;
-    const int32_t ntile = blockIdx.x;
     const int32_t k_tiles = K / kPackK;
     const int32_t per_wave = (k_tiles + NWAVES - 1) / NWAVES;
     const int32_t kt_begin = wave * per_wave;
@@ -870,6 +882,66 @@ extern "C" int mquant_w4_prepack(const uint8_t *w, uint8_t *out, int32_t N, int3
     return launch_status();
 }
 
+namespace mquant {
+
+// The tile GEMV for a group of linears that share xq (a group of one for the single-linear
+// entry points).  It handles 32 rows per pass; taller inputs (only reached for K % 128 != 0,
+// which the prefill kernel does not take) are walked in slabs of 32 rows.
+template <int EPI>
+int gemv_tile_dispatch(const int8_t *xq, int32_t T, int32_t K, GemvGroup grp, const Epilogue &ep,
+                       hipStream_t stream)
+{
+    int64_t total = 0;
+    for (int32_t i = 0; i < grp.n; ++i) {
+        grp.p[i].units = static_cast<int32_t>(ceil_div(grp.p[i].N, 32));
+        total += grp.p[i].units;
+    }
+    if (total <= 0 || total > 0x7fffffff) return MQUANT_ERR_BAD_SHAPE;
+    const unsigned n_tiles = static_cast<unsigned>(total);
+    for (int32_t t0 = 0; t0 < T; t0 += kGemvMaxT) {
+        const int32_t tt = T - t0 < kGemvMaxT ? T - t0 : kGemvMaxT;
+        Epilogue slab = ep;
+        int32_t nv = ep.n_vis - t0;
+        slab.n_vis = nv < 0 ? 0 : (nv > tt ? tt : nv);
+        if (ep.rows != nullptr) slab.rows = ep.rows + t0;
+        slab.xq = xq + static_cast<int64_t>(t0) * K;
+        const int8_t *xs = xq + static_cast<int64_t>(t0) * K;
+        GemvGroup gs = grp;
+        for (int32_t i = 0; i < grp.n; ++i) {
+            gs.p[i].y = grp.p[i].y + static_cast<int64_t>(t0) * grp.p[i].ldy;
+            gs.p[i].acc_out = grp.p[i].acc_out ? grp.p[i].acc_out + static_cast<int64_t>(t0) * grp.p[i].N : nullptr;
+        }
+        // Few n-tiles: more waves per tile to keep enough loads in flight.  Up to 16 rows:
+        // activations staged through LDS (faster at every T measured, T = 1 included:
+        // a batch then takes 1-4 activation loads instead of 8).
+        const int arows = tt > 16 ? 0 : (tt <= 4 ? 4 : (tt <= 8 ? 8 : 16));
+#define MQ_GEMV(NWV, AR)                                                                            \
+    MQ_LAUNCH((w4a8_gemv_kernel<NWV, 4, EPI, AR>), dim3(n_tiles), dim3(NWV * 64), 0, stream, xs, gs, \
+              tt, K, slab)
+        if (n_tiles >= 256) {
+            if (arows == 0) MQ_GEMV(8, 0);
+            else if (arows == 4) MQ_GEMV(8, 4);
+            else if (arows == 8) MQ_GEMV(8, 8);
+            else MQ_GEMV(8, 16);
+        } else {
+            if (arows == 0) MQ_GEMV(16, 0);
+            else if (arows == 4) MQ_GEMV(16, 4);
+            else if (arows == 8) MQ_GEMV(16, 8);
+            else MQ_GEMV(16, 16);
+        }
+#undef MQ_GEMV
+        const int ls = launch_status();
+        if (ls != MQUANT_OK) return ls;
+    }
+    return MQUANT_OK;
+}
+
+template int gemv_tile_dispatch<kEpiStatic>(const int8_t *, int32_t, int32_t, GemvGroup, const Epilogue &, hipStream_t);
+template int gemv_tile_dispatch<kEpiRowScale>(const int8_t *, int32_t, int32_t, GemvGroup, const Epilogue &, hipStream_t);
+template int gemv_tile_dispatch<kEpiSplit>(const int8_t *, int32_t, int32_t, GemvGroup, const Epilogue &, hipStream_t);
+
+}  // namespace mquant
+
 extern "C" int64_t mquant_w4a8_workspace_bytes(int32_t T, int32_t N, int32_t K)
 {
     if (T < 0 || N < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
@@ -900,44 +972,15 @@ int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void
         return gemv_stream_dispatch<EPI>(xq, T, K, grp, ep, stream);
     }
     if (T <= kGemvMaxT || K % 128 != 0) {
-        // GEMV handles 32 rows per pass; walk taller inputs in slabs of 32 rows
-        // (only reached for K % 128 != 0, which the prefill kernel does not take).
-        for (int32_t t0 = 0; t0 < T; t0 += kGemvMaxT) {
-            const int32_t tt = T - t0 < kGemvMaxT ? T - t0 : kGemvMaxT;
-            Epilogue slab = ep;
-            int32_t nv = ep.n_vis - t0;
-            slab.n_vis = nv < 0 ? 0 : (nv > tt ? tt : nv);
-            if (ep.rows != nullptr) slab.rows = ep.rows + t0;
-            slab.xq = xq + static_cast<int64_t>(t0) * K;
-            const unsigned n_tiles = static_cast<unsigned>(ceil_div(N, 32));
-            const int8_t *xs = xq + static_cast<int64_t>(t0) * K;
-            __half *ys = static_cast<__half *>(y) + static_cast<int64_t>(t0) * ldy;
-            int32_t *accs = acc_out ? acc_out + static_cast<int64_t>(t0) * N : nullptr;
-            // Few n-tiles: more waves per tile to keep enough loads in flight.  Up to 16 rows:
-            // activations staged through LDS (faster at every T measured, T = 1 included:
-            // a batch then takes 1-4 activation loads instead of 8).
-            const uint4 *wpp = reinterpret_cast<const uint4 *>(wp);
-            const __half *wsc = static_cast<const __half *>(w_scale);
-            const int arows = tt > 16 ? 0 : (tt <= 4 ? 4 : (tt <= 8 ? 8 : 16));
-#define MQ_GEMV(NWV, AR)                                                                        \
-    MQ_LAUNCH((w4a8_gemv_kernel<NWV, 4, EPI, AR>), dim3(n_tiles), dim3(NWV * 64), 0, stream, xs, \
-              wpp, wsc, ys, ldy, accs, tt, N, K, slab)
-            if (n_tiles >= 256) {
-                if (arows == 0) MQ_GEMV(8, 0);
-                else if (arows == 4) MQ_GEMV(8, 4);
-                else if (arows == 8) MQ_GEMV(8, 8);
-                else MQ_GEMV(8, 16);
-            } else {
-                if (arows == 0) MQ_GEMV(16, 0);
-                else if (arows == 4) MQ_GEMV(16, 4);
-                else if (arows == 8) MQ_GEMV(16, 8);
-                else MQ_GEMV(16, 16);
-            }
-#undef MQ_GEMV
-            const int ls = launch_status();
-            if (ls != MQUANT_OK) return ls;
-        }
-        return MQUANT_OK;
+        GemvGroup grp = {};
+        grp.n = 1;
+        grp.p[0].wp = reinterpret_cast<const uint4 *>(wp);
+        grp.p[0].w_scale = static_cast<const __half *>(w_scale);
+        grp.p[0].y = static_cast<__half *>(y);
+        grp.p[0].acc_out = acc_out;
+        grp.p[0].ldy = ldy;
+        grp.p[0].N = N;
+        return gemv_tile_dispatch<EPI>(xq, T, K, grp, ep, stream);
     }
     int splits = plan_splits(T, N, K);
     const int force_tile = tune_state().gemm_tile.load(std::memory_order_relaxed);

@@ -599,15 +599,8 @@ extern "C" int mquant_w4a8_gemv_grouped(const int8_t *xq, int32_t T, int32_t K, 
     ep.n_vis = n_vis, ep.s_vis = s_vis, ep.s_txt = s_txt, ep.K = K, ep.xq = xq;
     int64_t group_tiles = 0;
     for (int32_t i = 0; i < grp.n; ++i) group_tiles += ceil_div(grp.p[i].N, kPackN);
-    if (!gemv_stream_takes(T, K, group_tiles)) {
-        // outside the streaming kernel's range: one plain call per linear
-        for (int32_t i = 0; i < grp.n; ++i) {
-            const int st = mquant_w4a8_gemm(xq, reinterpret_cast<const uint8_t *>(grp.p[i].wp), grp.p[i].w_scale,
-                                            grp.p[i].y, grp.p[i].ldy, nullptr, T, grp.p[i].N, K, n_vis, s_vis,
-                                            s_txt, nullptr, 0, stream);
-            if (st != MQUANT_OK) return st;
-        }
-        return MQUANT_OK;
-    }
+    // outside the streaming kernels' range: the tile kernel, still one launch for the group
+    if (!gemv_stream_takes(T, K, group_tiles))
+        return gemv_tile_dispatch<kEpiStatic>(xq, T, K, grp, ep, static_cast<hipStream_t>(stream));
     return gemv_stream_dispatch<kEpiStatic>(xq, T, K, grp, ep, static_cast<hipStream_t>(stream));
 }

@@ -378,13 +378,15 @@ def test_gemv_small_shapes_full(mq, T):
     check_y(y.cpu().numpy(), ref, f"gemv T={T}")
 
 
-@pytest.mark.parametrize("T", [1, 3, 4, 7])
+@pytest.mark.parametrize("T", [1, 3, 4, 7, 16, 21, 32])
 @pytest.mark.parametrize("K,Ns", [(3584, (3584, 512, 512)), (1024, (18944, 18944)), (18944, (3584,)),
-                                  (384, (40, 0, 200, 72))])
+                                  (384, (40, 0, 200, 72)), (192, (100, 36))])
 def test_gemv_grouped_equals_the_oracle_per_linear(mq, T, K, Ns):
     """Several linears sharing one input in one launch (q/k/v; gate/up): every output of every
     linear against the oracle, bit for bit on the fp16 value (accumulators are checked through
-    the single-linear entry on the same kernel); untouched padding columns stay untouched."""
+    the single-linear entry on the same kernel); untouched padding columns stay untouched.
+    Up to 4 rows the streaming kernel takes the group, 5 to 16 rows it takes few-tile groups,
+    everything else (and K % 128 != 0) is one launch of the tile kernel."""
     say(f"grouped gemv T={T} K={K} Ns={Ns}")
     rng = np.random.default_rng(T * 1000 + K + len(Ns))
     xq = rng.integers(-128, 128, size=(T, K), dtype=np.int8)
