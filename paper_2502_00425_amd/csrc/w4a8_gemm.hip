@@ -784,14 +784,18 @@ int check_gemm_args(const void *xq, const void *wp, const void *w_scale, const v
 // the CUs and K is long, S work-groups share a tile's K range, write int32
 // partials to the workspace and a small second kernel reduces and dequantises.
 // (A single-kernel reduction needs device-scope fences, which write back the
-// whole L2 and were measured far slower.)
+// whole L2 and were measured far slower.)  Up to 16 pieces of at least 2048
+// channels: measured on the few-tile shapes of short prompts, 64..512 rows against
+// 18944 x 3584 take 34-51 us instead of 54-63 us with at most 4 pieces of 4096, and
+// nothing measured got slower; pieces shorter than 2048 channels lose to the fixed
+// cost of a work-group (3584-channel shapes stay unsplit).
 int plan_splits(int32_t T, int32_t N, int32_t K)
 {
     const int64_t tiles = ceil_div(T, 256) * ceil_div(N, 256);
     int64_t s = kNumCU / tiles;
     if (s < 2 || N % 4 != 0) return 1;
-    if (s > 4) s = 4;
-    while (s > 1 && K / s < 4096) --s;
+    if (s > 16) s = 16;
+    while (s > 1 && K / s < 2048) --s;
     return static_cast<int>(s);
 }
 
@@ -882,6 +886,24 @@ extern "C" int mquant_w4_prepack(const uint8_t *w, uint8_t *out, int32_t N, int3
     return launch_status();
 }
 
+namespace {
+
+// Shapes the tile GEMV takes instead of the prefill GEMM: up to 32 rows (one pass), every K
+// the prefill kernel does not handle, and short prompts against small matrices, where the
+// GEMM would run a single, mostly empty row of tiles at its fixed cost while the GEMV
+// re-reads a few MB of weights per 32-row slab (measured, 7B shapes at 33..64 rows:
+// 3584 x 3584 and 3584 x 4608 10-12 us against 22 us, 8192 x 8192 18-20 against 31 us;
+// at 96 rows 17 against 22 us for the first two; with more weights or rows the GEMM wins).
+bool gemv_tile_takes(int32_t T, int32_t N, int32_t K)
+{
+    if (T <= kGemvMaxT || K % 128 != 0) return true;
+    if (tune_state().gemm_tile.load(std::memory_order_relaxed) >= 0) return false;   // a forced GEMM tile
+    const int64_t weights = static_cast<int64_t>(N) * K;
+    return (T <= 64 && weights <= (int64_t{1} << 26)) || (T <= 96 && weights <= (int64_t{1} << 24));
+}
+
+}  // namespace
+
 namespace mquant {
 
 // The tile GEMV for a group of linears that share xq (a group of one for the single-linear
@@ -914,17 +936,17 @@ int gemv_tile_dispatch(const int8_t *xq, int32_t T, int32_t K, GemvGroup grp, co
         // Few n-tiles: more waves per tile to keep enough loads in flight.  Up to 16 rows:
         // activations staged through LDS (faster at every T measured, T = 1 included:
         // a batch then takes 1-4 activation loads instead of 8).
-        const int arows = tt > 16 ? 0 : (tt <= 4 ? 4 : (tt <= 8 ? 8 : 16));
+        const int arows = tt > 16 ? 32 : (tt <= 4 ? 4 : (tt <= 8 ? 8 : 16));
 #define MQ_GEMV(NWV, AR)                                                                            \
     MQ_LAUNCH((w4a8_gemv_kernel<NWV, 4, EPI, AR>), dim3(n_tiles), dim3(NWV * 64), 0, stream, xs, gs, \
               tt, K, slab)
         if (n_tiles >= 256) {
-            if (arows == 0) MQ_GEMV(8, 0);
+            if (arows == 32) MQ_GEMV(8, 32);
             else if (arows == 4) MQ_GEMV(8, 4);
             else if (arows == 8) MQ_GEMV(8, 8);
             else MQ_GEMV(8, 16);
         } else {
-            if (arows == 0) MQ_GEMV(16, 0);
+            if (arows == 32) MQ_GEMV(16, 32);
             else if (arows == 4) MQ_GEMV(16, 4);
             else if (arows == 8) MQ_GEMV(16, 8);
             else MQ_GEMV(16, 16);
@@ -946,7 +968,7 @@ extern "C" int64_t mquant_w4a8_workspace_bytes(int32_t T, int32_t N, int32_t K)
 {
     if (T < 0 || N < 0 || K < 0) return MQUANT_ERR_BAD_SHAPE;
     if (K % kPackK != 0 || K > kMaxK) return MQUANT_ERR_UNSUPPORTED;
-    if (T <= kGemvMaxT || K % 128 != 0) return 0;
+    if (gemv_tile_takes(T, N, K)) return 0;
     const int splits = plan_splits(T, N, K);
     return splits > 1 ? static_cast<int64_t>(splits) * T * N * 4 : 0;
 }
@@ -971,7 +993,7 @@ int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void
         grp.p[0].N = N;
         return gemv_stream_dispatch<EPI>(xq, T, K, grp, ep, stream);
     }
-    if (T <= kGemvMaxT || K % 128 != 0) {
+    if (gemv_tile_takes(T, N, K)) {
         GemvGroup grp = {};
         grp.n = 1;
         grp.p[0].wp = reinterpret_cast<const uint4 *>(wp);

@@ -439,6 +439,34 @@ def test_gemv_streamed_rows_full(mq, T, N, K):
     assert (yb[:, N:] == 9.0).all()
 
 
+@pytest.mark.parametrize("T,N,K", [(33, 3584, 3584), (64, 520, 1024), (65, 200, 640), (96, 4608, 3584),
+                                   (50, 8192, 8192), (40, 72, 18944), (97, 264, 1024)])
+def test_short_prompts_on_small_matrices(mq, T, N, K):
+    """33 to 96 rows against a small matrix run as 32-row slabs of the tile GEMV (the last slab
+    ragged), one row more or a larger matrix as the prefill GEMM: accumulators and fp16 bits of
+    every output on both sides of the switch, visual / text boundary inside a slab."""
+    say(f"short prompt T={T} N={N} K={K}")
+    rng = np.random.default_rng(T * 7 + N + K)
+    xq = rng.integers(-128, 128, size=(T, K), dtype=np.int8)
+    packed = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
+    V, s_vis, s_txt = T // 2 + 3, 0.2, 0.03
+    acc_want = orc.gemm_i8_i4_i32(xq, orc.unpack_w4(packed))
+    ref, y_want = orc.dequant(acc_want, V, s_vis, s_txt, w_scale)
+    wp = mq.w4_prepack(dev(packed))
+    ws_bytes = mq.w4a8_workspace_bytes(T, N, K)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    acc = torch.full((T, N), -7, dtype=torch.int32, device="cuda")
+    ybuf = torch.full((T, N + 8), 9.0, dtype=torch.float16, device="cuda")
+    mq.w4a8_gemm(dev(xq), wp, dev(w_scale), N, V, s_vis, s_txt, out=ybuf[:, :N], acc_out=acc, workspace=ws)
+    assert (acc.cpu().numpy() == acc_want).all()
+    yb = ybuf.cpu().numpy()
+    assert (yb[:, :N].view(np.uint16) == y_want.view(np.uint16)).all()
+    assert (yb[:, N:] == 9.0).all()
+    y2 = mq.w4a8_gemm(dev(xq), wp, dev(w_scale), N, V, s_vis, s_txt, workspace=ws)     # the path as timed
+    assert (y2.cpu().numpy().view(np.uint16) == y_want.view(np.uint16)).all()
+
+
 def test_gemv_grouped_argument_errors(mq):
     P = 0x1000
     L = mq.lib
