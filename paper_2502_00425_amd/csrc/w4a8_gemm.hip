@@ -497,11 +497,15 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(
 //
 // Several linears that share xq (q/k/v, gate/up) can go into one launch: the grid is the
 // concatenation of their tiles (units = 32-channel tiles of each problem).
-template <int NWAVES, int KT, int EPI, int AROWS>
+//
+// MROWS = 2 (33..64 rows, short prompts): two 32-row blocks share every weight tile -- the
+// weights are still read once, unpacked once and feed two MFMA pairs.
+template <int NWAVES, int KT, int EPI, int AROWS, int MROWS>
 __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
     const int8_t *__restrict__ xq, GemvGroup grp, int32_t T, int32_t K, Epilogue ep)
 {
     typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+    static_assert(MROWS == 1 || (MROWS == 2 && AROWS == 64), "two row blocks come with 64 staged rows");
     // which linear of the group, which tile of it
     int32_t pi = 0, ntile = blockIdx.x;
     while (pi + 1 < grp.n && ntile >= grp.p[pi].units) {
@@ -532,30 +536,34 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
     const int32_t n = ntile * 32 + l32;
     const __half ws_h = w_scale[n < N ? n : N - 1];      // requested early, used in the epilogue
 
-    v16i acc0, acc1;                                      // two chains: no back-to-back dependent MFMAs
+    v16i acc0[MROWS], acc1[MROWS];                        // two chains: no back-to-back dependent MFMAs
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        acc0[r] = 0;
-        acc1[r] = 0;
-    }
+    for (int m = 0; m < MROWS; ++m)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            acc0[m][r] = 0;
+            acc1[m][r] = 0;
+        }
     const uint4 *wtile = wp + static_cast<int64_t>(ntile) * k_tiles * 64 + lane;
     const int8_t *xrow = xq + static_cast<int64_t>(l32 < T ? l32 : T - 1) * K + g * 32;
 
     constexpr int NI = AROWS / 4;                         // staging loads per batch: 4 rows each
     uint8_t *patch = smem + wave * kWaveBytes;
     const int srow = lane >> 4, scol = lane & 15;
-    const int frag_row = l32 < T ? l32 : T - 1;
+    int frag_row[MROWS];
+#pragma unroll
+    for (int m = 0; m < MROWS; ++m) frag_row[m] = m * 32 + l32 < T ? m * 32 + l32 : T - 1;
 
     for (int32_t base = kt_begin; base < kt_end; base += KT) {
-        uint4 a0[KT], a1[KT], b[KT];
+        uint4 a0[MROWS][KT], a1[MROWS][KT], b[KT];
         v4u stage_reg[NI > 0 ? NI : 1];
         if constexpr (AROWS == 0) {
 #pragma unroll
             for (int u = 0; u < KT; ++u) {
                 int32_t kt = base + u;
                 kt = kt < kt_end ? kt : kt_end - 1;
-                a0[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64);
-                a1[u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64 + 16);
+                a0[0][u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64);
+                a1[0][u] = *reinterpret_cast<const uint4 *>(xrow + kt * 64 + 16);
             }
         } else {
             // 16 bytes per lane, 16 lanes per row; channels past K are clamped into the row
@@ -583,26 +591,31 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
             for (int i = 0; i < NI; ++i)
                 *reinterpret_cast<v4u *>(patch + (i * 4 + srow) * kPatchPitch + scol * 16) = stage_reg[i];
 #pragma unroll
-            for (int u = 0; u < KT; ++u) {
-                const uint8_t *f = patch + frag_row * kPatchPitch + u * 64 + g * 32;
-                a0[u] = *reinterpret_cast<const uint4 *>(f);
-                a1[u] = *reinterpret_cast<const uint4 *>(f + 16);
-            }
+            for (int m = 0; m < MROWS; ++m)
+#pragma unroll
+                for (int u = 0; u < KT; ++u) {
+                    const uint8_t *f = patch + frag_row[m] * kPatchPitch + u * 64 + g * 32;
+                    a0[m][u] = *reinterpret_cast<const uint4 *>(f);
+                    a1[m][u] = *reinterpret_cast<const uint4 *>(f + 16);
+                }
         }
 #pragma unroll
         for (int u = 0; u < KT; ++u) {
-            const uint32_t m = (base + u < kt_end) ? 0xFFFFFFFFu : 0u;     // wave-uniform
+            const uint32_t msk = (base + u < kt_end) ? 0xFFFFFFFFu : 0u;     // wave-uniform
             uint4 bb = b[u];
-            bb.x &= m;
-            bb.y &= m;
-            bb.z &= m;
-            bb.w &= m;
+            bb.x &= msk;
+            bb.y &= msk;
+            bb.z &= msk;
+            bb.w &= msk;
             v4i b0, b1;
             unpack_w4x16(bb, b0, b1);
-            acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a0[u]), b0, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a1[u]), b1, acc1, 0, 0, 0);
+#pragma unroll
+            for (int m = 0; m < MROWS; ++m) {
+                acc0[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a0[m][u]), b0, acc0[m], 0, 0, 0);
+                acc1[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(a1[m][u]), b1, acc1[m], 0, 0, 0);
+            }
         }
-        // Scheduling order inside a batch: all 3*KT memory reads first, then the
+        // Scheduling order inside a batch: all memory reads first, then the
         // arithmetic.  Without this the scheduler sinks each load next to its use
         // and the wave waits out one memory round trip per k-tile.
         if constexpr (AROWS == 0) {
@@ -610,28 +623,31 @@ __global__ __launch_bounds__(NWAVES * 64) void w4a8_gemv_kernel(
         } else {
             __builtin_amdgcn_sched_group_barrier(0x020, NI + KT, 0);
             __builtin_amdgcn_sched_group_barrier(0x200, NI, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2 * KT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * KT * MROWS, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x00A, 18 * KT, 0);
+        __builtin_amdgcn_sched_group_barrier(0x00A, (16 + 2 * MROWS) * KT, 0);
     }
     if constexpr (AROWS > 0) __syncthreads();             // the sums below reuse the patches
 
     // Accumulator register r of k-group g holds row acc_row(r, g): with T <= 8
     // only r < 4 can be a valid row, with T <= 16 only r < 8.
     const int rmax = T <= 8 ? 4 : (T <= 16 ? 8 : 16);
-#pragma unroll
-    for (int r = 0; r < 16; ++r)
-        if (r < rmax) red[wave][r][lane] = acc0[r] + acc1[r];
-    __syncthreads();
-
     const float ws = __half2float(ws_h);
-    for (int r = wave; r < rmax; r += NWAVES) {
-        const int32_t row = acc_row(r, g);
-        if (row < T && n < N) {
-            int32_t sum = 0;
 #pragma unroll
-            for (int w = 0; w < NWAVES; ++w) sum += red[w][r][lane];
-            store_out<EPI>(sum, row, n, ep, ws, y, ldy, acc_out, N);
+    for (int m = 0; m < MROWS; ++m) {
+        if (m > 0) __syncthreads();                       // the sums of the block before have been read
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (r < rmax) red[wave][r][lane] = acc0[m][r] + acc1[m][r];
+        __syncthreads();
+        for (int r = wave; r < rmax; r += NWAVES) {
+            const int32_t row = m * 32 + acc_row(r, g);
+            if (row < T && n < N) {
+                int32_t sum = 0;
+#pragma unroll
+                for (int w = 0; w < NWAVES; ++w) sum += red[w][r][lane];
+                store_out<EPI>(sum, row, n, ep, ws, y, ldy, acc_out, N);
+            }
         }
     }
 }
@@ -889,17 +905,21 @@ extern "C" int mquant_w4_prepack(const uint8_t *w, uint8_t *out, int32_t N, int3
 namespace {
 
 // Shapes the tile GEMV takes instead of the prefill GEMM: up to 32 rows (one pass), every K
-// the prefill kernel does not handle, and short prompts against small matrices, where the
-// GEMM would run a single, mostly empty row of tiles at its fixed cost while the GEMV
-// re-reads a few MB of weights per 32-row slab (measured, 7B shapes at 33..64 rows:
-// 3584 x 3584 and 3584 x 4608 10-12 us against 22 us, 8192 x 8192 18-20 against 31 us;
-// at 96 rows 17 against 22 us for the first two; with more weights or rows the GEMM wins).
+// the prefill kernel does not handle, and short prompts against matrices with few output
+// channels, where the GEMM would run a single, mostly empty row of tiles at its fixed cost
+// while the GEMV streams the weights once per 64 rows (two row blocks per weight tile).
+// Measured at 33..64 rows, GEMV against GEMM: 3584 x 3584 and 3584 x 4608 9 against 22 us,
+// 18944 x 3584 24-30 against 33-35, 8192 x 8192 15 against 31, 8192 x 10240 23-25 against 32,
+// 29568 x 8192 39-43 against 60; with 18944 or more output channels the GEMM fills enough
+// compute units to win (3584 x 18944: 22-23 us either way, x 37888: 38 against 32).  At
+// 65..128 rows the second pass pays for small matrices only (3584 x 3584: 14-16 against 22 us,
+// 8192 x 8192 24-29 against 34; 18944 x 3584 49 against 36).
 bool gemv_tile_takes(int32_t T, int32_t N, int32_t K)
 {
     if (T <= kGemvMaxT || K % 128 != 0) return true;
     if (tune_state().gemm_tile.load(std::memory_order_relaxed) >= 0) return false;   // a forced GEMM tile
-    const int64_t weights = static_cast<int64_t>(N) * K;
-    return (T <= 64 && weights <= (int64_t{1} << 26)) || (T <= 96 && weights <= (int64_t{1} << 24));
+    if (T <= 2 * kGemvMaxT) return N <= 12288;
+    return T <= 4 * kGemvMaxT && N <= 8192 && static_cast<int64_t>(N) * K <= (int64_t{1} << 26);
 }
 
 }  // namespace
@@ -920,8 +940,11 @@ int gemv_tile_dispatch(const int8_t *xq, int32_t T, int32_t K, GemvGroup grp, co
     }
     if (total <= 0 || total > 0x7fffffff) return MQUANT_ERR_BAD_SHAPE;
     const unsigned n_tiles = static_cast<unsigned>(total);
-    for (int32_t t0 = 0; t0 < T; t0 += kGemvMaxT) {
-        const int32_t tt = T - t0 < kGemvMaxT ? T - t0 : kGemvMaxT;
+    // 32 rows per pass, 64 with two row blocks per weight tile (rows beyond 32 come here only
+    // for short prompts and for K % 128 != 0)
+    for (int32_t t0 = 0; t0 < T;) {
+        const int32_t left = T - t0;
+        const int32_t tt = left > kGemvMaxT ? (left < 2 * kGemvMaxT ? left : 2 * kGemvMaxT) : left;
         Epilogue slab = ep;
         int32_t nv = ep.n_vis - t0;
         slab.n_vis = nv < 0 ? 0 : (nv > tt ? tt : nv);
@@ -933,27 +956,30 @@ int gemv_tile_dispatch(const int8_t *xq, int32_t T, int32_t K, GemvGroup grp, co
             gs.p[i].y = grp.p[i].y + static_cast<int64_t>(t0) * grp.p[i].ldy;
             gs.p[i].acc_out = grp.p[i].acc_out ? grp.p[i].acc_out + static_cast<int64_t>(t0) * grp.p[i].N : nullptr;
         }
-        // Few n-tiles: more waves per tile to keep enough loads in flight.  Up to 16 rows:
-        // activations staged through LDS (faster at every T measured, T = 1 included:
-        // a batch then takes 1-4 activation loads instead of 8).
-        const int arows = tt > 16 ? 32 : (tt <= 4 ? 4 : (tt <= 8 ? 8 : 16));
-#define MQ_GEMV(NWV, AR)                                                                            \
-    MQ_LAUNCH((w4a8_gemv_kernel<NWV, 4, EPI, AR>), dim3(n_tiles), dim3(NWV * 64), 0, stream, xs, gs, \
-              tt, K, slab)
-        if (n_tiles >= 256) {
-            if (arows == 32) MQ_GEMV(8, 32);
-            else if (arows == 4) MQ_GEMV(8, 4);
-            else if (arows == 8) MQ_GEMV(8, 8);
-            else MQ_GEMV(8, 16);
+        // Few n-tiles: more waves per tile to keep enough loads in flight.  The activations of
+        // a batch are staged through LDS (faster at every T measured, T = 1 included:
+        // a batch then takes 1-16 row loads instead of 8 scattered fragment loads).
+        const int arows = tt > 32 ? 64 : (tt > 16 ? 32 : (tt <= 4 ? 4 : (tt <= 8 ? 8 : 16)));
+#define MQ_GEMV(NWV, AR, MR)                                                                          \
+    MQ_LAUNCH((w4a8_gemv_kernel<NWV, 4, EPI, AR, MR>), dim3(n_tiles), dim3(NWV * 64), 0, stream, xs, \
+              gs, tt, K, slab)
+        if (arows == 64) {
+            MQ_GEMV(8, 64, 2);
+        } else if (n_tiles >= 256) {
+            if (arows == 32) MQ_GEMV(8, 32, 1);
+            else if (arows == 4) MQ_GEMV(8, 4, 1);
+            else if (arows == 8) MQ_GEMV(8, 8, 1);
+            else MQ_GEMV(8, 16, 1);
         } else {
-            if (arows == 32) MQ_GEMV(16, 32);
-            else if (arows == 4) MQ_GEMV(16, 4);
-            else if (arows == 8) MQ_GEMV(16, 8);
-            else MQ_GEMV(16, 16);
+            if (arows == 32) MQ_GEMV(16, 32, 1);
+            else if (arows == 4) MQ_GEMV(16, 4, 1);
+            else if (arows == 8) MQ_GEMV(16, 8, 1);
+            else MQ_GEMV(16, 16, 1);
         }
 #undef MQ_GEMV
         const int ls = launch_status();
         if (ls != MQUANT_OK) return ls;
+        t0 += tt;
     }
     return MQUANT_OK;
 }

@@ -440,11 +440,14 @@ def test_gemv_streamed_rows_full(mq, T, N, K):
 
 
 @pytest.mark.parametrize("T,N,K", [(33, 3584, 3584), (64, 520, 1024), (65, 200, 640), (96, 4608, 3584),
-                                   (50, 8192, 8192), (40, 72, 18944), (97, 264, 1024)])
+                                   (50, 8192, 8192), (40, 72, 18944), (128, 264, 1024), (127, 40, 256),
+                                   (129, 264, 1024), (70, 9000, 128), (60, 12320, 256), (64, 12288, 128)])
 def test_short_prompts_on_small_matrices(mq, T, N, K):
-    """33 to 96 rows against a small matrix run as 32-row slabs of the tile GEMV (the last slab
-    ragged), one row more or a larger matrix as the prefill GEMM: accumulators and fp16 bits of
-    every output on both sides of the switch, visual / text boundary inside a slab."""
+    """33 to 64 rows against a matrix with few output channels (up to 128 rows against a small
+    one) run as 64-row passes of the tile GEMV, two row blocks per weight tile, the last pass
+    ragged or a plain 32-row one; one row or one tile column more runs as the prefill GEMM.
+    Accumulators and fp16 bits of every output on both sides of each switch, the visual / text
+    boundary inside a pass."""
     say(f"short prompt T={T} N={N} K={K}")
     rng = np.random.default_rng(T * 7 + N + K)
     xq = rng.integers(-128, 128, size=(T, K), dtype=np.int8)
