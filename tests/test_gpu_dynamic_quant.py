@@ -79,9 +79,21 @@ def test_dynquant_rejects_rows_too_long_for_registers(mq):
 
 
 @pytest.mark.parametrize("T,N,K,B", [(1, 200, 832, 64), (16, 200, 832, 64), (75, 300, 1024, 512),
-                                     (300, 520, 8192, 128), (260, 264, 3584, 512)])
-def test_dynamic_linear_end_to_end(mq, T, N, K, B):
-    """Rotate + per-token quantize + GEMM (GEMV, both GEMM tiles, split-K) + per-token dequant."""
+                                     (140, 300, 1024, 512), (300, 520, 8192, 128), (260, 264, 3584, 512)])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2])
+def test_dynamic_linear_end_to_end(mq, T, N, K, B, tile):
+    """Rotate + per-token quantize + GEMM + per-token dequant: the library's own choice of kernel
+    (GEMV, the 64-row GEMV passes of short prompts, GEMM, split-K) and every GEMM tile forced."""
+    if tile >= 0 and T <= 32:
+        pytest.skip("decode shapes never reach the GEMM")
+    mq.tune_set(mq.TUNE_GEMM_TILE, tile)
+    try:
+        _dynamic_linear_case(mq, T, N, K, B)
+    finally:
+        mq.tune_set(mq.TUNE_GEMM_TILE, -1)
+
+
+def _dynamic_linear_case(mq, T, N, K, B):
     say(f"dynamic linear T={T} N={N} K={K}")
     rng = np.random.default_rng(T + N + K)
     x = make_x(rng, T, K)

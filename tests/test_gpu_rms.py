@@ -57,8 +57,9 @@ def check(y_gpu, ref, mag, what):
 
 @pytest.mark.parametrize("T,N,K,B,n_split", [
     (1, 200, 832, 64, 1), (16, 200, 832, 64, 3),            # GEMV
-    (75, 300, 1024, 512, 2),                                 # 128x256 tile, narrow stores
-    (260, 264, 3584, 512, 1), (260, 520, 3584, 512, 7),      # 256x256 tile, wide stores
+    (75, 300, 1024, 512, 2),                                 # short prompt: GEMV pass of 64 rows + one of 11
+    (140, 300, 1024, 512, 2),                                # GEMM, narrow stores
+    (260, 264, 3584, 512, 1), (260, 520, 3584, 512, 7),      # GEMM, wide stores
     (300, 520, 8192, 128, 5),                                # split-K + reduce kernel
     (40, 64, 18944, 512, 37),                                # every block flagged
     (33, 96, 8192, 128, 64),                                 # the most the entry point takes
@@ -80,6 +81,32 @@ def test_rms_gemm_matches_oracle(mq, T, N, K, B, n_split):
     check(y.cpu().numpy(), ref, mag, "rms with acc_out")
     y2 = mq.w4a8_gemm_rms(*args)
     check(y2.cpu().numpy(), ref, mag, "rms")
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2])
+def test_rms_on_every_gemm_tile(mq, tile):
+    """The split epilogue on each compiled GEMM tile (forced through the tuning hook; a forced
+    tile also keeps short prompts on the GEMM): ragged rows and columns, narrow and wide stores."""
+    rng = np.random.default_rng(70 + tile)
+    mq.tune_set(mq.TUNE_GEMM_TILE, tile)
+    try:
+        for T, N, K, B, n_split in [(75, 300, 1024, 512, 2), (200, 264, 640, 128, 5)]:
+            say(f"rms tile {tile} T={T} N={N} K={K}")
+            xq, wq, idx, wsplit, ssplit, w_scale = make_case(rng, T, N, K, B, n_split)
+            V, s_vis, s_txt = T // 3, 0.11, 0.004
+            acc_want = orc.gemm_i8_i4_i32(xq, wq)
+            ref, _ = orc.dequant_rms(acc_want, xq, V, s_vis, s_txt, w_scale, idx, wsplit, ssplit)
+            main, _ = orc.dequant(acc_want, V, s_vis, s_txt, w_scale)
+            mag = np.abs(main) + np.abs(ref - main)
+            wp = mq.w4_prepack(dev(pack_int4(wq)))
+            args = (dev(xq), wp, dev(w_scale), N, V, s_vis, s_txt, idx, dev(wsplit), ssplit)
+            acc = torch.empty((T, N), dtype=torch.int32, device="cuda")
+            y = mq.w4a8_gemm_rms(*args, acc_out=acc)
+            assert (acc.cpu().numpy() == acc_want).all()
+            check(y.cpu().numpy(), ref, mag, f"rms tile {tile} with acc_out")
+            check(mq.w4a8_gemm_rms(*args).cpu().numpy(), ref, mag, f"rms tile {tile}")
+    finally:
+        mq.tune_set(mq.TUNE_GEMM_TILE, -1)
 
 
 def test_rms_without_split_channels_equals_plain_gemm(mq):
