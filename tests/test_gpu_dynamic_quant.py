@@ -78,14 +78,15 @@ def test_dynquant_rejects_rows_too_long_for_registers(mq):
     assert e.value.status == mq.ERR_UNSUPPORTED
 
 
-@pytest.mark.parametrize("T,N,K,B", [(1, 200, 832, 64), (16, 200, 832, 64), (75, 300, 1024, 512),
-                                     (140, 300, 1024, 512), (300, 520, 8192, 128), (260, 264, 3584, 512)])
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2])
+_DYN_SHAPES = [(1, 200, 832, 64), (16, 200, 832, 64), (75, 300, 1024, 512), (140, 300, 1024, 512),
+               (300, 520, 8192, 128), (260, 264, 3584, 512)]
+
+
+# decode shapes never reach the GEMM, so they run with the library's own choice only
+@pytest.mark.parametrize("T,N,K,B,tile", [s + (t,) for s in _DYN_SHAPES for t in (-1, 0, 1, 2) if t < 0 or s[0] > 32])
 def test_dynamic_linear_end_to_end(mq, T, N, K, B, tile):
     """Rotate + per-token quantize + GEMM + per-token dequant: the library's own choice of kernel
     (GEMV, the 64-row GEMV passes of short prompts, GEMM, split-K) and every GEMM tile forced."""
-    if tile >= 0 and T <= 32:
-        pytest.skip("decode shapes never reach the GEMM")
     mq.tune_set(mq.TUNE_GEMM_TILE, tile)
     try:
         _dynamic_linear_case(mq, T, N, K, B)
