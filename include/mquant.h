@@ -491,7 +491,8 @@ int mquant_w4g128_gemm(const void *x_dev, int64_t ldx, const uint8_t *w_prepacke
  * ---------------------------------------------------------------------- */
 
 typedef enum {
-    MQUANT_TUNE_GEMM_TILE = 0,      /* -1 = cost model; 0 = 256x256, 1 = 128x256, 2 = 192x128 */
+    MQUANT_TUNE_GEMM_TILE = 0,      /* -1 = cost model; 0 = 256x256, 1 = 128x256, 2 = 192x128,
+                                       3 = 64x128, 4 = 64x256 (short prompts) */
     MQUANT_TUNE_GEMM_NOSPLIT = 1,   /* 0 = cost model; 1 = never split K */
     MQUANT_TUNE_G128_TILE = 2,      /* -1 = cost model; 0 = 128x256, 1 = 96x256 (weight-only GEMM) */
     MQUANT_TUNE_GEMV_VARIANT = 3    /* -1 = default; 0..3 = waves per work-group x loads in flight per

@@ -24,7 +24,7 @@ extern "C" int mquant_tune_set(int32_t key, int32_t value)
     TuneState &t = tune_state();
     switch (key) {
     case MQUANT_TUNE_GEMM_TILE:
-        if (value < -1 || value > 2) return MQUANT_ERR_BAD_SHAPE;
+        if (value < -1 || value > 4) return MQUANT_ERR_BAD_SHAPE;
         t.gemm_tile.store(value, std::memory_order_relaxed);
         return MQUANT_OK;
     case MQUANT_TUNE_GEMM_NOSPLIT:

@@ -861,8 +861,21 @@ int launch_gemm(const int8_t *xq, const uint8_t *wp, const void *w_scale, void *
 // hides one group's prologue and epilogue under the other's main loop and
 // halves the tile-count granularity.  Cost model: rounds over the 256 CUs times
 // tile area, the smaller tile derated by its measured relative rate.
+//
+// Short prompts on matrices with many output channels (up to 128 rows; the few-channel ones
+// go to the tile GEMV): one or two rows of 64-row tiles, three stages, several work-groups per
+// CU.  With one row of 128- or 256-row tiles the k-loop of a lone, mostly empty work-group per
+// CU sets the time.  Measured at T = 64, 64x128 / 64x256 against the 128x256 tile the cost
+// model below would pick: 3584 -> 18944 15.3 / 19.1 against 22.6 us, 3584 -> 37888 23.0 / 20.7
+// against 32.7, 8192 -> 59136 53.6 / 48.9 against 72.8; at T = 128: 3584 -> 18944 20.5
+// against 23.2, 8192 -> 10240 28.4 against 37.9, 3584 -> 37888 no difference (30.5).
 int pick_gemm_tile(int32_t T, int32_t N)
 {
+    if (T <= 128) {
+        const int64_t groups = ceil_div(T, 64) * ceil_div(N, 128);       // of 64x128 tiles
+        if (T <= 64) return groups <= kNumCU ? 3 : 4;
+        if (groups <= kNumCU + kNumCU / 4) return 3;
+    }
     // rounds of work-groups over the CUs x tile area / measured relative efficiency of the tile
     const double a = static_cast<double>(ceil_div(ceil_div(T, 256) * ceil_div(N, 256), kNumCU)) *
                      256.0 * 256.0;
@@ -1041,6 +1054,12 @@ int gemm_dispatch(const int8_t *xq, const uint8_t *wp, const void *w_scale, void
                                                  static_cast<int32_t *>(workspace), stream);
     }
     const int tile = force_tile < 0 ? pick_gemm_tile(T, N) : force_tile;
+    if (tile == 3)
+        return launch_gemm<64, 128, 2, 4, 3, EPI>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, ep, 1,
+                                                nullptr, stream);
+    if (tile == 4)
+        return launch_gemm<64, 256, 1, 8, 3, EPI>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, ep, 1,
+                                                nullptr, stream);
     if (tile == 0)
         return launch_gemm<256, 256, 2, 4, 3, EPI>(xq, wp, w_scale, y, ldy, acc_out, T, N, K, ep, 1,
                                                  nullptr, stream);

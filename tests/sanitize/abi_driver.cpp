@@ -55,7 +55,7 @@ int main()
         CHECK(mquant_static_scale_from_absmax(-1.0f, 16, 8, &s) == MQUANT_ERR_BAD_SHAPE);
         CHECK(mquant_static_scale_from_absmax(1.0f, 16, 8, nullptr) == MQUANT_ERR_NULL);
         CHECK(mquant_tune_set(99, 0) == MQUANT_ERR_BAD_SHAPE);
-        CHECK(mquant_tune_set(MQUANT_TUNE_GEMM_TILE, 3) == MQUANT_ERR_BAD_SHAPE);
+        CHECK(mquant_tune_set(MQUANT_TUNE_GEMM_TILE, 5) == MQUANT_ERR_BAD_SHAPE);
         CHECK(mquant_tune_set(MQUANT_TUNE_GEMM_TILE, 2) == MQUANT_OK && mquant_tune_set(MQUANT_TUNE_GEMM_TILE, -1) == MQUANT_OK);
         CHECK(mquant_tune_set(MQUANT_TUNE_GEMV_VARIANT, 4) == MQUANT_ERR_BAD_SHAPE);
     }

@@ -224,7 +224,7 @@ def test_static_scale_is_computed_by_the_library_and_matches_the_oracle():
 def test_tune_hook_validates_and_resets():
     f = mq.lib.mquant_tune_set
     assert f(99, 0) == mq.ERR_BAD_SHAPE
-    assert f(mq.TUNE_GEMM_TILE, 3) == mq.ERR_BAD_SHAPE
+    assert f(mq.TUNE_GEMM_TILE, 5) == mq.ERR_BAD_SHAPE
     assert f(mq.TUNE_GEMM_TILE, -2) == mq.ERR_BAD_SHAPE
     assert f(mq.TUNE_GEMM_NOSPLIT, 2) == mq.ERR_BAD_SHAPE
     assert f(mq.TUNE_G128_TILE, 2) == mq.ERR_BAD_SHAPE

@@ -83,7 +83,7 @@ _DYN_SHAPES = [(1, 200, 832, 64), (16, 200, 832, 64), (75, 300, 1024, 512), (140
 
 
 # decode shapes never reach the GEMM, so they run with the library's own choice only
-@pytest.mark.parametrize("T,N,K,B,tile", [s + (t,) for s in _DYN_SHAPES for t in (-1, 0, 1, 2) if t < 0 or s[0] > 32])
+@pytest.mark.parametrize("T,N,K,B,tile", [s + (t,) for s in _DYN_SHAPES for t in (-1, 0, 1, 2, 3, 4) if t < 0 or s[0] > 32])
 def test_dynamic_linear_end_to_end(mq, T, N, K, B, tile):
     """Rotate + per-token quantize + GEMM + per-token dequant: the library's own choice of kernel
     (GEMV, the 64-row GEMV passes of short prompts, GEMM, split-K) and every GEMM tile forced."""

@@ -441,11 +441,14 @@ def test_gemv_streamed_rows_full(mq, T, N, K):
 
 @pytest.mark.parametrize("T,N,K", [(33, 3584, 3584), (64, 520, 1024), (65, 200, 640), (96, 4608, 3584),
                                    (50, 8192, 8192), (40, 72, 18944), (128, 264, 1024), (127, 40, 256),
-                                   (129, 264, 1024), (70, 9000, 128), (60, 12320, 256), (64, 12288, 128)])
+                                   (129, 264, 1024), (70, 9000, 128), (60, 12320, 256), (64, 12288, 128),
+                                   (50, 18944, 384), (64, 37888, 256), (33, 33000, 128), (100, 18944, 256),
+                                   (128, 10240, 384), (128, 37888, 128)])
 def test_short_prompts_on_small_matrices(mq, T, N, K):
     """33 to 64 rows against a matrix with few output channels (up to 128 rows against a small
     one) run as 64-row passes of the tile GEMV, two row blocks per weight tile, the last pass
-    ragged or a plain 32-row one; one row or one tile column more runs as the prefill GEMM.
+    ragged or a plain 32-row one; one row or one tile column more runs as the prefill GEMM,
+    which takes 64-row tiles (64x128 or 64x256 by the number of work-groups) up to 128 rows.
     Accumulators and fp16 bits of every output on both sides of each switch, the visual / text
     boundary inside a pass."""
     say(f"short prompt T={T} N={N} K={K}")
@@ -892,7 +895,7 @@ def test_prefill_step_as_hip_graph_replays_match_plain_launches(mq):
             assert torch.equal(a, b), f"replay {rep} differs from the plain launches"
 
 
-@pytest.mark.parametrize("tile,name", [(0, "256x256"), (1, "128x256"), (2, "192x128")])
+@pytest.mark.parametrize("tile,name", [(0, "256x256"), (1, "128x256"), (2, "192x128"), (3, "64x128"), (4, "64x256")])
 def test_every_gemm_tile_on_ragged_shapes(mq, tile, name, forced_tile):
     """The dispatcher picks a tile from a cost model; this forces each compiled tile in turn
     (the tuning hook of the library) so that all of them see ragged T and N, one k-block and

@@ -83,7 +83,7 @@ def test_rms_gemm_matches_oracle(mq, T, N, K, B, n_split):
     check(y2.cpu().numpy(), ref, mag, "rms")
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 def test_rms_on_every_gemm_tile(mq, tile):
     """The split epilogue on each compiled GEMM tile (forced through the tuning hook; a forced
     tile also keeps short prompts on the GEMM): ragged rows and columns, narrow and wide stores."""
